@@ -1,0 +1,412 @@
+"""Pins of the float64 oracle against things other than itself (CPU only).
+
+Nothing here calls the HIP path.  Each test names what fixes the expected value:
+brute-force sums of eq. (3), numpy's FFT as the textbook special case, closed forms of
+single-mode inputs, invariants (linearity, Parseval, shift equivariance, adjoint identity)
+and central finite differences for every gradient.
+"""
+import math
+
+import numpy as np
+import pytest
+
+from oracle import fno_oracle as O
+
+
+def _rng(*key):
+    return np.random.default_rng(list(key))
+
+
+def _rand_layer(seed, spec, b=2, cin=2, cout=3):
+    rng = _rng(seed, 1)
+    lx, ly, lz, lt = [len(k) for k in O.mode_lists(spec)]
+    x = rng.standard_normal((b, cin) + spec.grid)
+    r = rng.standard_normal((cin, cout, lx, ly, lz, lt)) + 1j * rng.standard_normal((cin, cout, lx, ly, lz, lt))
+    return x, r
+
+
+def _rel(a, b):
+    return np.linalg.norm(np.ravel(a - b)) / max(np.linalg.norm(np.ravel(b)), 1e-300)
+
+
+TINY = [
+    O.LayerSpec((6, 4, 4, 6), (2, 1, 2, 3), 0),     # even sizes, mt below Nyquist
+    O.LayerSpec((4, 6, 4, 4), (2, 2, 1, 3), 0),     # mt = Nt/2+1: Nyquist bin kept
+    O.LayerSpec((5, 3, 4, 5), (2, 1, 1, 3), 0),     # odd sizes, odd Nt (no Nyquist bin exists)
+    O.LayerSpec((5, 4, 3, 6), (1, 1, 1, 2), 1),     # symmetric rule -m..m
+    O.LayerSpec((4, 4, 6, 7), (2, 2, 3, 4), 0),     # full spatial sets, odd Nt full half-spectrum
+]
+
+
+# ------------------------------------------------------------------ mode sets (A1, A5)
+def test_mode_lists_literal():
+    assert O.spatial_modes(16, 4, 0) == [0, 1, 2, 3, -4, -3, -2, -1]
+    assert O.spatial_modes(16, 4, 1) == [0, 1, 2, 3, 4, -4, -3, -2, -1]
+    assert O.temporal_modes(8, 3) == [0, 1, 2]
+    assert O.temporal_modes(16, 9) == list(range(9))
+    with pytest.raises(ValueError):
+        O.temporal_modes(16, 10)
+    with pytest.raises(ValueError):
+        O.spatial_modes(6, 4, 0)
+    # the five workloads' retained counts
+    for grid, modes, want in [((16, 16, 16, 8), (4, 4, 4, 3), (8, 8, 8, 3)),
+                              ((64, 64, 64, 16), (12, 12, 12, 8), (24, 24, 24, 8)),
+                              ((128, 128, 64, 32), (16, 16, 12, 9), (32, 32, 24, 9)),
+                              ((256, 256, 128, 32), (24, 24, 16, 9), (48, 48, 32, 9)),
+                              ((128, 128, 128, 16), (16, 16, 16, 9), (32, 32, 32, 9))]:
+        got = tuple(len(k) for k in O.mode_lists(O.LayerSpec(grid, modes, 0)))
+        assert got == want
+
+
+def test_hermitian_weights_literal():
+    assert O.hermitian_weights(8, [0, 1, 2, 3, 4]).tolist() == [1, 2, 2, 2, 1]
+    assert O.hermitian_weights(7, [0, 1, 2, 3]).tolist() == [1, 2, 2, 2]
+    assert O.hermitian_weights(16, [0, 1, 2]).tolist() == [1, 2, 2]
+
+
+# ------------------------------------------------------------------ P1 brute force
+@pytest.mark.parametrize("spec", TINY)
+def test_P1_definition_equals_brute_force(spec):
+    x, r = _rand_layer(11, spec)
+    assert _rel(O.forward_spectrum(x, spec), O.brute_forward_spectrum(x, spec)) < 1e-12
+    yh = O.mix_modes(O.forward_spectrum(x, spec), r)
+    assert _rel(O.inverse_spectrum(yh, spec), O.brute_inverse_spectrum(yh, spec)) < 1e-12
+    assert _rel(O.spectral_conv_fwd(x, r, spec), O.brute_spectral_conv(x, r, spec)) < 1e-12
+
+
+# ------------------------------------------------------------------ P2 library FFT special case
+def _lib_spectral_conv(x, r, spec):
+    """rfftn -> gather kept modes -> mix -> scatter into zeros -> irfftn (numpy only)."""
+    kx, ky, kz, kt = O.mode_lists(spec)
+    nx, ny, nz, nt = spec.grid
+    full = np.fft.rfftn(x, axes=(-4, -3, -2, -1))
+    ix = np.mod(kx, nx)
+    iy = np.mod(ky, ny)
+    iz = np.mod(kz, nz)
+    it = np.asarray(kt)
+    kept = full[:, :, ix][:, :, :, iy][:, :, :, :, iz][:, :, :, :, :, it]
+    yh = np.einsum("bixyzt,ioxyzt->boxyzt", kept, r)
+    big = np.zeros((x.shape[0], r.shape[1], nx, ny, nz, nt // 2 + 1), complex)
+    big[np.ix_(range(x.shape[0]), range(r.shape[1]), ix, iy, iz, it)] = yh
+    return np.fft.irfftn(big, s=spec.grid, axes=(-4, -3, -2, -1)), kept
+
+
+@pytest.mark.parametrize("spec", TINY + [O.LayerSpec((16, 16, 16, 8), (4, 4, 4, 3), 0),
+                                          O.LayerSpec((12, 10, 9, 11), (3, 2, 4, 5), 1)])
+def test_P2_equals_numpy_fft_route(spec):
+    x, r = _rand_layer(12, spec)
+    want, kept = _lib_spectral_conv(x, r, spec)
+    got, xhat = O.spectral_conv_fwd(x, r, spec, return_xhat=True)
+    assert _rel(xhat, kept) < 1e-12
+    assert _rel(got, want) < 1e-12
+
+
+# ------------------------------------------------------------------ P3 linearity
+def test_P3_linear_in_input_and_weights():
+    spec = TINY[0]
+    x1, r1 = _rand_layer(13, spec)
+    x2, r2 = _rand_layer(14, spec)
+    a, b = 0.7, -1.9
+    lhs = O.spectral_conv_fwd(a * x1 + b * x2, r1, spec)
+    rhs = a * O.spectral_conv_fwd(x1, r1, spec) + b * O.spectral_conv_fwd(x2, r1, spec)
+    assert _rel(lhs, rhs) < 1e-12
+    lhs = O.spectral_conv_fwd(x1, a * r1 + b * r2, spec)
+    rhs = a * O.spectral_conv_fwd(x1, r1, spec) + b * O.spectral_conv_fwd(x1, r2, spec)
+    assert _rel(lhs, rhs) < 1e-12
+
+
+# ------------------------------------------------------------------ P4 identity and Parseval
+@pytest.mark.parametrize("grid", [(4, 6, 4, 8), (6, 4, 2, 6)])
+def test_P4_full_mode_set_is_identity_and_parseval(grid):
+    spec = O.LayerSpec(grid, (grid[0] // 2, grid[1] // 2, grid[2] // 2, grid[3] // 2 + 1), 0)
+    rng = _rng(15)
+    x = rng.standard_normal((1, 1) + grid)
+    r = np.ones((1, 1) + tuple(len(k) for k in O.mode_lists(spec)), complex)
+    assert _rel(O.spectral_conv_fwd(x, r, spec), x) < 1e-12
+    xhat = O.forward_spectrum(x, spec)
+    c = O.hermitian_weights(grid[3], O.mode_lists(spec)[3])
+    assert abs(np.sum(x * x) - np.sum(c * np.abs(xhat) ** 2) / spec.npoints) < 1e-10 * np.sum(x * x)
+
+
+def test_P4_identity_odd_sizes_symmetric_rule():
+    grid = (5, 3, 7, 5)
+    spec = O.LayerSpec(grid, (2, 1, 3, 3), 1)
+    x = _rng(16).standard_normal((1, 1) + grid)
+    r = np.ones((1, 1) + tuple(len(k) for k in O.mode_lists(spec)), complex)
+    assert _rel(O.spectral_conv_fwd(x, r, spec), x) < 1e-12
+
+
+# ------------------------------------------------------------------ P5 single-mode closed forms
+def _theta(spec, k4):
+    nx, ny, nz, nt = spec.grid
+    g = np.meshgrid(*[np.arange(n) for n in spec.grid], indexing="ij")
+    return 2 * math.pi * (k4[0] * g[0] / nx + k4[1] * g[1] / ny + k4[2] * g[2] / nz + k4[3] * g[3] / nt)
+
+
+def _one_hot_r(spec, k4, val):
+    lists = O.mode_lists(spec)
+    r = np.zeros((1, 1) + tuple(len(k) for k in lists), complex)
+    idx = tuple(lists[a].index(k4[a]) for a in range(4))
+    r[(0, 0) + idx] = val
+    return r
+
+
+def test_P5a_interior_mode_rotates_and_scales_a_cosine():
+    spec = O.LayerSpec((8, 6, 8, 8), (3, 2, 3, 4), 0)
+    rw = 0.8 * np.exp(1j * 0.6)
+    for k4 in [(2, -1, 1, 2), (-3, 1, -2, 1), (0, 0, 0, 3), (1, 1, -3, 3)]:
+        phi = 0.37
+        x = np.cos(_theta(spec, k4) + phi)[None, None]
+        y = O.spectral_conv_fwd(x, _one_hot_r(spec, k4, rw), spec)
+        want = abs(rw) * np.cos(_theta(spec, k4) + phi + np.angle(rw))
+        assert np.max(np.abs(y[0, 0] - want)) < 1e-13
+
+
+def test_P5b_kt0_mode_is_halved_unless_partner_carries_conjugate():
+    spec = O.LayerSpec((8, 6, 8, 8), (3, 2, 3, 4), 0)
+    rw = 1.3 * np.exp(-1j * 1.1)
+    k4 = (2, -1, 1, 0)
+    neg = (-2, 1, -1, 0)
+    phi = -0.52
+    x = np.cos(_theta(spec, k4) + phi)[None, None]
+    y = O.spectral_conv_fwd(x, _one_hot_r(spec, k4, rw), spec)
+    want = 0.5 * abs(rw) * np.cos(_theta(spec, k4) + phi + np.angle(rw))
+    assert np.max(np.abs(y[0, 0] - want)) < 1e-13
+    r = _one_hot_r(spec, k4, rw) + _one_hot_r(spec, neg, np.conj(rw))
+    y = O.spectral_conv_fwd(x, r, spec)
+    assert np.max(np.abs(y[0, 0] - 2 * want)) < 1e-13
+    # DC: a constant field is scaled by Re(r)
+    y = O.spectral_conv_fwd(np.full((1, 1) + spec.grid, 1.7), _one_hot_r(spec, (0, 0, 0, 0), rw), spec)
+    assert np.max(np.abs(y - rw.real * 1.7)) < 1e-13
+
+
+def test_P5c_nyquist_mode():
+    # kt = Nt/2 kept: cos(pi*nt + spatial phase) behaves like a kt=0 plane (weight c = 1)
+    spec = O.LayerSpec((4, 4, 4, 6), (2, 2, 2, 4), 0)
+    rw = 0.9 * np.exp(1j * 0.4)
+    k4 = (1, 0, -1, 3)
+    x = np.cos(_theta(spec, k4) + 0.2)[None, None]
+    y = O.spectral_conv_fwd(x, _one_hot_r(spec, k4, rw), spec)
+    want = 0.5 * abs(rw) * np.cos(_theta(spec, k4) + 0.2 + np.angle(rw))
+    assert np.max(np.abs(y[0, 0] - want)) < 1e-13
+
+
+# ------------------------------------------------------------------ P6 truncation exactness
+def test_P6_only_kept_frequencies_pass():
+    spec = O.LayerSpec((6, 4, 4, 6), (2, 1, 1, 2), 0)
+    lists = O.mode_lists(spec)
+    kept = {(a, b, c, d) for a in lists[0] for b in lists[1] for c in lists[2] for d in lists[3]}
+    r = np.ones((1, 1) + tuple(len(k) for k in lists), complex)
+    nx, ny, nz, nt = spec.grid
+
+    for ax in range(nx):
+        for ay in range(ny):
+            for az in range(nz):
+                for at in range(nt // 2 + 1):
+                    x = np.cos(_theta(spec, (ax, ay, az, at)))[None, None]
+                    y = O.spectral_conv_fwd(x, r, spec)
+                    reps = []
+                    for s in (+1, -1):
+                        kt_ = s * at
+                        if kt_ % nt > nt // 2:
+                            continue
+                        kk = ((s * ax) % nx, (s * ay) % ny, (s * az) % nz, kt_ % nt)
+                        reps.append(kk)
+                    hit = False
+                    for kk in reps:
+                        for cand in kept:
+                            if (cand[0] % nx, cand[1] % ny, cand[2] % nz, cand[3]) == kk:
+                                hit = True
+                    if hit:
+                        assert np.max(np.abs(y)) > 1e-3
+                    else:
+                        assert np.max(np.abs(y)) < 1e-12
+
+
+def test_one_hot_weight_lights_the_matching_frequency():
+    # A5: entry (jx,jy,jz,jt) of R acts on frequency (kx[jx], ky[jy], kz[jz], kt[jt])
+    spec = O.LayerSpec((8, 8, 8, 8), (2, 2, 2, 3), 0)
+    lists = O.mode_lists(spec)
+    j = (3, 1, 2, 2)                       # -> k = (-1, 1, -2, 2)
+    k4 = tuple(lists[a][j[a]] for a in range(4))
+    assert k4 == (-1, 1, -2, 2)
+    r = np.zeros((1, 1, 4, 4, 4, 3), complex)
+    r[(0, 0) + j] = 1.0
+    x = _rng(21).standard_normal((1, 1) + spec.grid)
+    y = O.spectral_conv_fwd(x, r, spec)
+    spec_full = np.fft.fftn(y[0, 0])
+    mag = np.abs(spec_full)
+    peak = np.unravel_index(np.argmax(mag), mag.shape)
+    want_a = tuple(np.mod(k4, spec.grid))
+    want_b = tuple(np.mod([-v for v in k4], spec.grid))
+    assert peak in (want_a, want_b)
+    mask = np.ones_like(mag, bool)
+    mask[want_a] = False
+    mask[want_b] = False
+    assert np.max(mag[mask]) < 1e-9 * mag[peak]
+
+
+# ------------------------------------------------------------------ P7 zero weights
+def test_P7_zero_weights_give_zero_and_block_reduces_to_pointwise():
+    spec = TINY[1]
+    x, r = _rand_layer(17, spec, cin=3, cout=3)
+    assert np.all(O.spectral_conv_fwd(x, 0 * r, spec) == 0.0)
+    rng = _rng(18)
+    w = rng.standard_normal((3, 3))
+    b = rng.standard_normal(3)
+    out, z, _ = O.block_fwd(x, 0 * r, w, b, spec)
+    zz = np.zeros_like(x)
+    for bb in range(x.shape[0]):
+        for o in range(3):
+            zz[bb, o] = b[o] + sum(w[o, i] * x[bb, i] for i in range(3))
+    assert _rel(z, zz) < 1e-14
+    from scipy.stats import norm
+    assert _rel(out, zz * norm.cdf(zz)) < 1e-13
+
+
+def test_gelu_textbook_values():
+    # Phi(1) = 0.8413447460685429 (standard normal table); sigma(z) - sigma(-z) = z
+    assert abs(O.gelu(np.array(1.0)) - 0.8413447460685429) < 1e-15
+    assert abs(O.gelu(np.array(-1.0)) + 0.15865525393145707) < 1e-15
+    assert O.gelu(np.array(0.0)) == 0.0
+    z = np.linspace(-6, 6, 101)
+    assert np.max(np.abs(O.gelu(z) - O.gelu(-z) - z)) < 1e-14
+    h = 1e-6
+    fd = (O.gelu(z + h) - O.gelu(z - h)) / (2 * h)
+    assert np.max(np.abs(fd - O.gelu_prime(z))) < 1e-9
+
+
+# ------------------------------------------------------------------ P8 Hermitian weights -> real inverse
+def test_P8_hermitian_weights_make_complex_inverse_real():
+    spec = O.LayerSpec((6, 5, 4, 6), (2, 2, 1, 2), 1)
+    lists = O.mode_lists(spec)
+    x, r = _rand_layer(19, spec, b=1, cin=1, cout=1)
+    # enforce R(-k_xyz, kt=0) = conj(R(k_xyz, kt=0))
+    for ax, fa in enumerate(lists[0]):
+        for ay, fb in enumerate(lists[1]):
+            for az, fc in enumerate(lists[2]):
+                pa, pb, pc = lists[0].index(-fa), lists[1].index(-fb), lists[2].index(-fc)
+                r[0, 0, pa, pb, pc, 0] = np.conj(r[0, 0, ax, ay, az, 0])
+    r[0, 0, 0, 0, 0, 0] = r[0, 0, 0, 0, 0, 0].real        # the self-paired DC entry must be real
+    yh = O.mix_modes(O.forward_spectrum(x, spec), r)[0, 0, :, :, :, 0]
+    ex = O.dft_matrix(6, lists[0], +1.0)
+    ey = O.dft_matrix(5, lists[1], +1.0)
+    ez = O.dft_matrix(4, lists[2], +1.0)
+    v = np.einsum("xyz,xa,yb,zc->abc", yh, ex, ey, ez)
+    assert np.max(np.abs(v.imag)) < 1e-12 * np.max(np.abs(v.real))
+
+
+# ------------------------------------------------------------------ P9 shift equivariance / convolution theorem
+def test_P9_shift_equivariance():
+    spec = TINY[2]
+    x, r = _rand_layer(20, spec)
+    y = O.spectral_conv_fwd(x, r, spec)
+    for axis, s in [(-4, 2), (-3, 1), (-2, 3), (-1, 2)]:
+        ys = O.spectral_conv_fwd(np.roll(x, s, axis=axis), r, spec)
+        assert _rel(ys, np.roll(y, s, axis=axis)) < 1e-12
+
+
+def test_P9_circular_convolution_with_kernel():
+    spec = O.LayerSpec((4, 3, 4, 6), (1, 1, 2, 3), 0)
+    x, r = _rand_layer(22, spec, b=1, cin=1, cout=1)
+    y = O.spectral_conv_fwd(x, r, spec)[0, 0]
+    delta = np.zeros((1, 1) + spec.grid)
+    delta[0, 0, 0, 0, 0, 0] = 1.0
+    kappa = O.spectral_conv_fwd(delta, r, spec)[0, 0]
+    nx, ny, nz, nt = spec.grid
+    want = np.zeros(spec.grid)
+    for a in range(nx):
+        for b in range(ny):
+            for c in range(nz):
+                for d in range(nt):
+                    want += x[0, 0, a, b, c, d] * np.roll(kappa, (a, b, c, d), axis=(0, 1, 2, 3))
+    assert _rel(y, want) < 1e-12
+
+
+# ------------------------------------------------------------------ P10 adjoint identity
+@pytest.mark.parametrize("spec", TINY)
+def test_P10_adjoint_is_layer_with_conjugate_transposed_weights(spec):
+    x, r = _rand_layer(23, spec, b=2, cin=2, cout=3)
+    y = _rng(24).standard_normal((2, 3) + spec.grid)
+    rh = np.conj(np.swapaxes(r, 0, 1))
+    lhs = np.sum(O.spectral_conv_fwd(x, r, spec) * y)
+    rhs = np.sum(x * O.spectral_conv_fwd(y, rh, spec))
+    assert abs(lhs - rhs) < 1e-12 * abs(lhs)
+    gx, _ = O.spectral_conv_bwd(x, r, y, spec)
+    assert _rel(gx, O.spectral_conv_fwd(y, rh, spec)) < 1e-12
+
+
+# ------------------------------------------------------------------ P11 gradients by finite differences
+@pytest.mark.parametrize("spec,activation", [(TINY[0], "gelu"), (TINY[1], "gelu"), (TINY[2], "gelu"),
+                                              (TINY[3], "identity")])
+def test_P11_block_gradients_match_central_differences(spec, activation):
+    rng = _rng(25)
+    x, r = _rand_layer(26, spec, b=2, cin=2, cout=2)
+    w = rng.standard_normal((2, 2))
+    b = rng.standard_normal(2)
+    target = rng.standard_normal(x.shape)
+
+    def loss(x_, r_, w_, b_):
+        out, _, _ = O.block_fwd(x_, r_, w_, b_, spec, activation)
+        return O.mse_loss(out, target)
+
+    out, _, _ = O.block_fwd(x, r, w, b, spec, activation)
+    g = O.block_bwd(x, r, w, b, O.mse_grad(out, target), spec, activation)
+    h = 1e-6
+    pick = _rng(27)
+
+    def check(arr, grad, rebuild, n=12, complex_part=None):
+        flat_idx = pick.choice(arr.size, size=min(n, arr.size), replace=False)
+        for fi in flat_idx:
+            idx = np.unravel_index(fi, arr.shape)
+            d = np.zeros_like(arr)
+            d[idx] = h if complex_part != "im" else 1j * h
+            fd = (loss(*rebuild(arr + d)) - loss(*rebuild(arr - d))) / (2 * h)
+            an = grad[idx] if complex_part is None else (grad[idx].real if complex_part == "re" else grad[idx].imag)
+            assert abs(fd - an) < 1e-9 + 1e-6 * abs(an), (idx, fd, an)
+
+    check(x, g["gx"], lambda v: (v, r, w, b))
+    check(w, g["gW"], lambda v: (x, r, v, b))
+    check(b, g["gb"], lambda v: (x, r, w, v))
+    check(r, g["gR"], lambda v: (x, v, w, b), complex_part="re")
+    check(r, g["gR"], lambda v: (x, v, w, b), complex_part="im")
+    # entries on the kt = 0 plane explicitly (they carry the half weight)
+    r0 = r.copy()
+    idx0 = (0, 1, 1, 0, 1, 0)
+    for part in ("re", "im"):
+        d = np.zeros_like(r0)
+        d[idx0] = h if part == "re" else 1j * h
+        fd = (loss(x, r0 + d, w, b) - loss(x, r0 - d, w, b)) / (2 * h)
+        an = g["gR"][idx0].real if part == "re" else g["gR"][idx0].imag
+        assert abs(fd - an) < 1e-9 + 1e-6 * abs(an)
+
+
+# ------------------------------------------------------------------ full-size helpers equal the plain routines
+def test_separable_spectrum_and_point_sampled_inverse_match_plain_routines():
+    spec = O.LayerSpec((6, 5, 8, 6), (2, 2, 3, 3), 0)
+    rng = _rng(28)
+    f = [rng.integers(-15, 16, size=(2, 3, n)) / 8.0 for n in spec.grid]
+    x = (f[0][:, :, :, None, None, None] * f[1][:, :, None, :, None, None]
+         * f[2][:, :, None, None, :, None] * f[3][:, :, None, None, None, :])
+    assert _rel(O.separable_forward_spectrum(*f, spec), O.forward_spectrum(x, spec)) < 1e-12
+    yh = O.forward_spectrum(x, spec)
+    full = O.inverse_spectrum(yh, spec)
+    pts = np.array([[0, 0, 0, 0], [5, 4, 7, 5], [2, 3, 1, 4], [3, 0, 6, 2]])
+    got = O.inverse_at_points(yh, spec, pts)
+    for p, (a, b, c, d) in enumerate(pts):
+        assert np.max(np.abs(got[..., p] - full[..., a, b, c, d])) < 1e-13
+
+
+def test_network_pieces():
+    spec = O.LayerSpec((4, 4, 4, 4), (1, 1, 1, 2), 0)
+    rng = _rng(29)
+    a = rng.standard_normal((1, 3) + spec.grid)
+    lw, lb = rng.standard_normal((4, 3)), rng.standard_normal(4)
+    v = O.pointwise_linear(a, lw, lb)
+    assert abs(v[0, 2, 1, 2, 3, 0] - (lb[2] + lw[2] @ a[0, :, 1, 2, 3, 0])) < 1e-13
+    w1, b1 = rng.standard_normal((6, 4)), rng.standard_normal(6)
+    w2, b2 = rng.standard_normal((1, 6)), rng.standard_normal(1)
+    u = O.pointwise_mlp2(v, w1, b1, w2, b2)
+    hvec = w1 @ v[0, :, 3, 1, 0, 2] + b1
+    from scipy.stats import norm
+    assert abs(u[0, 0, 3, 1, 0, 2] - (w2 @ (hvec * norm.cdf(hvec)) + b2)[0]) < 1e-13
