@@ -1,0 +1,142 @@
+/*
+ * fno.h -- C ABI of libfno: the 4D (x,y,z,t) Fourier-neural-operator spectral convolution
+ * and FNO block, forward and adjoint, as hand-written HIP kernels for gfx950 (MI355X).
+ *
+ * What the calls compute follows the paper's statement of the layer
+ * (Grady et al., "Model-Parallel Fourier Neural Operators ...", arXiv 2204.01205):
+ *   - eq. (2), Sec. 1.4 and the block update of Sec. 2.4:  nu_{k+1} = sigma(W nu_k + K(phi) nu_k)
+ *   - eq. (3), Sec. 1.4:  K(phi) nu = F^{-1}( R_phi . F nu ), R_phi = low-pass restriction to a
+ *     user-chosen number of modes per dimension plus a learned complex weight per kept mode
+ *   - eq. (4), Sec. 2.2:  y = W x + b contracted along the channel dimension
+ *   - eq. (7), Sec. 2.3 and the Fig. 5 caption: F^T is the adjoint (inverse) transform, used
+ *     for the backward pass
+ *
+ * Conventions (all calls):
+ *   - Tensors are dense, row-major, layout NCXYZT (Sec. 3.1): x[b][c][nx][ny][nz][nt], t contiguous.
+ *   - Every data pointer is a DEVICE pointer owned by the caller.  The library never allocates,
+ *     frees or synchronises; scratch comes from the caller's workspace `ws` (device memory,
+ *     256-byte aligned, at least fno_workspace_bytes() bytes).  Descriptors are host structs
+ *     read during the call only.
+ *   - Work is enqueued on `stream` (a hipStream_t passed as void*, NULL = default stream) and
+ *     the call returns without waiting.
+ *   - Complex tensors are interleaved (re, im) float pairs.
+ *   - Return value: FNO_OK (0) or a negative FNO_E* code.  On an argument error nothing is
+ *     launched and no output byte is written.
+ *   - Two calls that share a workspace or an output must be ordered by the caller.
+ *
+ * Kept modes.  With modes = (mx, my, mz, mt) the spatial axes keep the signed frequencies
+ *   rule 0:  0..m-1, -m..-1      (L = 2m)        rule 1:  0..m, -m..-1     (L = 2m+1)
+ * in exactly this order along the weight tensor's mode axes, and the real-transform axis t
+ * keeps 0..mt-1.  Requirements: 1 <= L <= N on x,y,z and 1 <= mt <= Nt/2 + 1.
+ *
+ * Forward transform is unnormalised; the inverse carries 1/(Nx Ny Nz Nt) and is a complex
+ * inverse over x,y,z followed by a complex-to-real step over t, i.e.
+ *   y[n] = (1/N) Re sum_k c_kt Yhat[k] exp(+i theta(k,n)),   c_kt = 1 for kt = 0 and kt = Nt/2, else 2.
+ */
+#ifndef FNO_H_
+#define FNO_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+enum {
+  FNO_OK = 0,
+  FNO_EINVAL = -1,        /* null required pointer, non-positive size, too many modes, bad flag  */
+  FNO_EUNSUPPORTED = -2,  /* valid request outside what the kernels cover (see fno_status_string) */
+  FNO_ENOSPC = -3,        /* workspace too small or misaligned                                    */
+  FNO_EHIP = -4           /* the HIP runtime refused a launch or copy                             */
+};
+
+enum { FNO_ACT_IDENTITY = 0, FNO_ACT_GELU = 1 };   /* GELU in its exact erf form */
+
+enum {
+  FNO_OP_SPECTRAL_CONV_FWD = 0,
+  FNO_OP_SPECTRAL_CONV_BWD = 1,
+  FNO_OP_BLOCK_FWD = 2,
+  FNO_OP_BLOCK_BWD = 3
+};
+
+enum {
+  FNO_FLAG_MSE_TARGET = 1  /* block_bwd: `gout` holds a target field; the upstream gradient is that of
+                              the mean squared error, 2 (sigma(z) - target) / (B Cout N)            */
+};
+
+typedef struct {
+  int32_t batch;       /* B >= 1                                                      */
+  int32_t c_in;        /* input channel width                                         */
+  int32_t c_out;       /* output channel width (<= 32 for the block calls)            */
+  int32_t grid[4];     /* Nx, Ny, Nz, Nt                                              */
+  int32_t modes[4];    /* mx, my, mz: per-side count on x,y,z ; mt: count on t        */
+  int32_t mode_rule;   /* 0 or 1, see above                                           */
+  int32_t activation;  /* FNO_ACT_*; used by the block calls only                     */
+  int32_t flags;       /* FNO_FLAG_* bits                                             */
+} fno_desc;
+
+/* Size in bytes of the workspace the given FNO_OP_* needs for this descriptor (host-only). */
+int fno_workspace_bytes(const fno_desc* desc, int op, size_t* bytes);
+
+/* Kept signed frequencies of axis 0..3 (x,y,z,t) in weight-tensor order (host-only).
+ * out_k (host, nullable) receives *out_n values; out_n (host) receives the count. */
+int fno_mode_indices(const fno_desc* desc, int axis, int32_t* out_k, int32_t* out_n);
+
+/* Spectral convolution, eq. (3):  y = K(phi) x.
+ *   x         in   float  [B][Cin][Nx][Ny][Nz][Nt]
+ *   R         in   cfloat [Cin][Cout][Lx][Ly][Lz][mt]
+ *   y         out  float  [B][Cout][Nx][Ny][Nz][Nt]
+ *   xhat_save out  cfloat [B][Cin][Lx][Ly][Lz][mt], nullable: the kept forward spectrum F x */
+int fno_spectral_conv_fwd(const fno_desc* desc, const float* x, const float* R, float* y,
+                          float* xhat_save, void* ws, size_t ws_bytes, void* stream);
+
+/* Adjoint of the spectral convolution (eq. (7): the transposed transform chain).
+ *   x          in  float, used only when xhat_saved is NULL (then F x is recomputed)
+ *   xhat_saved in  cfloat [B][Cin][Lx][Ly][Lz][mt], nullable
+ *   gy         in  float  [B][Cout][grid]     dL/dy
+ *   gx         out float  [B][Cin][grid]      dL/dx, nullable
+ *   gR         out cfloat [Cin][Cout][modes]  dL/dRe R + i dL/dIm R, nullable (overwritten) */
+int fno_spectral_conv_bwd(const fno_desc* desc, const float* x, const float* xhat_saved,
+                          const float* R, const float* gy, float* gx, float* gR,
+                          void* ws, size_t ws_bytes, void* stream);
+
+/* One FNO block, eq. (2):  out = sigma(W x + b + K(phi) x), Cin == Cout.
+ *   W  in float [Cout][Cin]     b  in float [Cout], nullable (= 0)
+ *   out        out float [B][Cout][grid]
+ *   z_save     out float [B][Cout][grid], nullable: the pre-activation, needed by fno_block_bwd
+ *   xhat_save  out cfloat, nullable, as above */
+int fno_block_fwd(const fno_desc* desc, const float* x, const float* R, const float* W,
+                  const float* b, float* out, float* z_save, float* xhat_save,
+                  void* ws, size_t ws_bytes, void* stream);
+
+/* Adjoint of the block.  z_saved is the pre-activation from fno_block_fwd; gout is dL/dout, or
+ * with FNO_FLAG_MSE_TARGET the target field of a mean-squared-error loss.
+ *   gx out float [B][Cin][grid], gR out cfloat [Cin][Cout][modes], gW out float [Cout][Cin],
+ *   gb out float [Cout]; each nullable, each overwritten.  gW and gb are sums over all batch
+ *   entries and grid points (the adjoint of broadcasting W and b, Sec. 2.1), reduced in a fixed
+ *   order so repeated calls give identical bits. */
+int fno_block_bwd(const fno_desc* desc, const float* x, const float* R, const float* W,
+                  const float* z_saved, const float* xhat_saved, const float* gout,
+                  float* gx, float* gR, float* gW, float* gb,
+                  void* ws, size_t ws_bytes, void* stream);
+
+/* Channel lift of Sec. 2.4 (eq. (11)):  y[b][o][p] = sum_i W[o][i] x[b][i][p] + bias[o] over
+ * npoints contiguous points per channel.  bias nullable.  c_out <= 32. */
+int fno_pointwise_linear(int32_t batch, int32_t c_in, int32_t c_out, int64_t npoints,
+                         const float* x, const float* W, const float* bias, float* y, void* stream);
+
+/* Projection to the output channels (end of Sec. 2.4) through one hidden layer, fused per point:
+ *   y = W2 gelu(W1 x + b1) + b2,  W1 [hidden][c_in], W2 [c_out][hidden].  The hidden tensor is
+ * never stored.  c_in <= 32, c_out <= 4. */
+int fno_pointwise_mlp2(int32_t batch, int32_t c_in, int32_t hidden, int32_t c_out, int64_t npoints,
+                       const float* x, const float* W1, const float* b1, const float* W2,
+                       const float* b2, float* y, void* stream);
+
+/* Text for a status code; for FNO_EHIP / FNO_EUNSUPPORTED the calling thread's last detail. */
+const char* fno_status_string(int status);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* FNO_H_ */

@@ -1,0 +1,335 @@
+// C ABI of libfno: argument checks, the per-call plan (how each axis is split, how the
+// workspace is carved up) and the kernel sequence.  See include/fno.h for the contract.
+#include "../../include/fno.h"
+#include "fno_kernels.h"
+
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+
+namespace {
+
+using fno::AxisPlan;
+
+thread_local char g_detail[256] = "";
+
+void set_detail(const char* fmt, ...) {
+  va_list ap;
+  va_start(ap, fmt);
+  std::vsnprintf(g_detail, sizeof(g_detail), fmt, ap);
+  va_end(ap);
+}
+
+struct Plan {
+  int B, Ci, Co;
+  int N[4], L[4], npos[4];
+  AxisPlan ax[3];        // x, y, z
+  int mt, Nt;
+  int64_t K;             // kept modes per (batch, channel)
+  int64_t Npts;          // grid points per (batch, channel)
+  // workspace offsets in bytes
+  size_t off_twt, off_tw[3], off_a1, off_a2, off_s1, off_s2, off_s3, off_gz, off_part, total;
+  int part_blocks;
+};
+
+size_t align_up(size_t v) { return (v + 255) & ~size_t(255); }
+
+int largest_pow2_divisor(int n, int cap) {
+  int m = 1;
+  while (m * 2 <= cap && n % (m * 2) == 0) m *= 2;
+  return m;
+}
+
+// Validates the descriptor and builds the plan.  need_block: Cin == Cout and Cout <= 32.
+int make_plan(const fno_desc* d, bool need_block, bool need_bwd_block, Plan* p) {
+  if (d == nullptr) { set_detail("descriptor is null"); return FNO_EINVAL; }
+  if (d->batch < 1 || d->c_in < 1 || d->c_out < 1) { set_detail("batch and channel widths must be >= 1"); return FNO_EINVAL; }
+  if (d->mode_rule != 0 && d->mode_rule != 1) { set_detail("mode_rule must be 0 or 1"); return FNO_EINVAL; }
+  if (d->activation != FNO_ACT_IDENTITY && d->activation != FNO_ACT_GELU) { set_detail("unknown activation"); return FNO_EINVAL; }
+  if (d->flags & ~FNO_FLAG_MSE_TARGET) { set_detail("unknown flag bits"); return FNO_EINVAL; }
+  for (int a = 0; a < 4; ++a) {
+    if (d->grid[a] < 1) { set_detail("grid sizes must be >= 1"); return FNO_EINVAL; }
+    if (d->modes[a] < (a == 3 ? 1 : 0)) { set_detail("mode counts must be non-negative (mt >= 1)"); return FNO_EINVAL; }
+  }
+  p->B = d->batch; p->Ci = d->c_in; p->Co = d->c_out;
+  for (int a = 0; a < 3; ++a) {
+    const int m = d->modes[a];
+    const long long L = d->mode_rule == 0 ? 2LL * m : 2LL * m + 1;
+    if (L < 1 || L > d->grid[a]) { set_detail("kept modes on a spatial axis must satisfy 1 <= L <= N (axis %d)", a); return FNO_EINVAL; }
+    p->N[a] = d->grid[a]; p->L[a] = (int)L;
+    p->npos[a] = d->mode_rule == 0 ? m : m + 1;
+  }
+  if (d->modes[3] > d->grid[3] / 2 + 1) { set_detail("mt must be <= Nt/2 + 1"); return FNO_EINVAL; }
+  p->N[3] = d->grid[3]; p->L[3] = d->modes[3]; p->npos[3] = d->modes[3];
+  p->Nt = d->grid[3]; p->mt = d->modes[3];
+  if (need_block && d->c_in != d->c_out) { set_detail("block calls need c_in == c_out"); return FNO_EINVAL; }
+
+  p->K = (int64_t)p->L[0] * p->L[1] * p->L[2] * p->L[3];
+  p->Npts = (int64_t)p->N[0] * p->N[1] * p->N[2] * p->N[3];
+  const int Cm = p->Ci > p->Co ? p->Ci : p->Co;
+  if (Cm > fno::kMaxCo) { set_detail("channel width above %d is not covered", fno::kMaxCo); return FNO_EUNSUPPORTED; }
+
+  for (int a = 0; a < 2; ++a) {
+    AxisPlan ap{p->N[a], p->L[a], p->npos[a], 1, p->N[a]};
+    ap.M = largest_pow2_divisor(p->N[a], fno::kMaxFftM);
+    ap.P = p->N[a] / ap.M;
+    if (!fno::axis_fits(ap)) { set_detail("spatial axis too long for the LDS tile (axis %d)", a); return FNO_EUNSUPPORTED; }
+    p->ax[a] = ap;
+  }
+  {
+    AxisPlan az{p->N[2], p->L[2], p->npos[2], 1, p->N[2]};
+    bool ok = false;
+    for (int m = largest_pow2_divisor(p->N[2], fno::kMaxFftM); m >= 1; m >>= 1) {
+      az.M = m; az.P = p->N[2] / m;
+      if (fno::tz_fwd_fits(az, p->Nt, p->mt) && fno::zt_inv_fits(az, p->Nt, p->mt, Cm)) { ok = true; break; }
+    }
+    if (!ok) { set_detail("an Nz x Nt plane with this many channels does not fit the LDS tiles"); return FNO_EUNSUPPORTED; }
+    p->ax[2] = az;
+  }
+  if (need_bwd_block && (p->Co * p->Ci + p->Co > 512)) { set_detail("weight-gradient reduction covers Cout*(Cin+1) <= 512"); return FNO_EUNSUPPORTED; }
+
+  // workspace
+  size_t off = 0;
+  p->off_twt = off; off = align_up(off + (size_t)p->mt * p->Nt * 8);
+  for (int a = 0; a < 3; ++a) { p->off_tw[a] = off; off = align_up(off + (size_t)p->ax[a].L * p->ax[a].P * 8); }
+  const size_t bc = (size_t)p->B * Cm;
+  p->off_a1 = off; off = align_up(off + bc * p->N[0] * p->N[1] * p->L[2] * p->mt * 8);
+  p->off_a2 = off; off = align_up(off + bc * p->N[0] * p->L[1] * p->L[2] * p->mt * 8);
+  p->off_s1 = off; off = align_up(off + bc * (size_t)p->K * 8);
+  p->off_s2 = off; off = align_up(off + bc * (size_t)p->K * 8);
+  p->off_s3 = off; off = align_up(off + bc * (size_t)p->K * 8);
+  p->off_gz = off;
+  p->off_part = off;
+  p->part_blocks = 0;
+  if (need_bwd_block) {
+    off = align_up(off + (size_t)p->B * p->Co * (size_t)p->Npts * 4);
+    p->off_part = off;
+    p->part_blocks = fno::bwd_pointwise_blocks(p->B, p->Npts);
+    off = align_up(off + (size_t)p->part_blocks * (p->Co * p->Ci + p->Co) * 8);
+  }
+  p->total = off;
+  return FNO_OK;
+}
+
+int check_ws(const Plan& p, void* ws, size_t ws_bytes) {
+  if (ws == nullptr) { set_detail("workspace is null"); return FNO_EINVAL; }
+  if ((reinterpret_cast<uintptr_t>(ws) & 255) != 0) { set_detail("workspace must be 256-byte aligned"); return FNO_ENOSPC; }
+  if (ws_bytes < p.total) { set_detail("workspace too small: need %lld bytes", (long long)p.total); return FNO_ENOSPC; }
+  return FNO_OK;
+}
+
+#define FNO_HIP(expr)                                                       \
+  do {                                                                      \
+    hipError_t e_ = (expr);                                                 \
+    if (e_ != hipSuccess) {                                                 \
+      set_detail("HIP error: %s", hipGetErrorString(e_));          \
+      return FNO_EHIP;                                                      \
+    }                                                                       \
+  } while (0)
+
+template <class T> T* at(void* ws, size_t off) { return reinterpret_cast<T*>(static_cast<char*>(ws) + off); }
+
+int build_tables(const Plan& p, void* ws, hipStream_t s) {
+  FNO_HIP(fno::launch_t_table(at<float2>(ws, p.off_twt), p.Nt, p.mt, s));
+  for (int a = 0; a < 3; ++a) FNO_HIP(fno::launch_axis_table(at<float2>(ws, p.off_tw[a]), p.ax[a], s));
+  return FNO_OK;
+}
+
+// real field [B*C][grid] -> kept spectrum [B*C][K]
+int forward_chain(const Plan& p, void* ws, const float* field, int C, float2* spec, hipStream_t s) {
+  const int64_t bc = (int64_t)p.B * C;
+  float2* a1 = at<float2>(ws, p.off_a1);
+  float2* a2 = at<float2>(ws, p.off_a2);
+  FNO_HIP(fno::launch_tz_fwd(field, a1, at<float2>(ws, p.off_twt), at<float2>(ws, p.off_tw[2]),
+                             bc * p.N[0] * p.N[1], p.ax[2], p.Nt, p.mt, s));
+  const int64_t in_y = (int64_t)p.L[2] * p.mt;
+  FNO_HIP(fno::launch_axis_fwd(a1, a2, at<float2>(ws, p.off_tw[1]), bc * p.N[0], p.ax[1], in_y, s));
+  const int64_t in_x = in_y * p.L[1];
+  FNO_HIP(fno::launch_axis_fwd(a2, spec, at<float2>(ws, p.off_tw[0]), bc, p.ax[0], in_x, s));
+  return FNO_OK;
+}
+
+// scaled spectrum [B*C][K] -> real field through the epilogue
+int inverse_chain(const Plan& p, void* ws, const float2* spec, int C, float* out, fno::Epilogue ep,
+                  hipStream_t s) {
+  const int64_t bc = (int64_t)p.B * C;
+  float2* a1 = at<float2>(ws, p.off_a1);
+  float2* a2 = at<float2>(ws, p.off_a2);
+  const int64_t in_y = (int64_t)p.L[2] * p.mt;
+  const int64_t in_x = in_y * p.L[1];
+  FNO_HIP(fno::launch_axis_inv(spec, a2, at<float2>(ws, p.off_tw[0]), bc, p.ax[0], in_x, s));
+  FNO_HIP(fno::launch_axis_inv(a2, a1, at<float2>(ws, p.off_tw[1]), bc * p.N[0], p.ax[1], in_y, s));
+  FNO_HIP(fno::launch_zt_inv(a1, out, at<float2>(ws, p.off_twt), at<float2>(ws, p.off_tw[2]), p.B, C,
+                             p.N[0], p.N[1], p.ax[2], p.Nt, p.mt, ep, s));
+  return FNO_OK;
+}
+
+int conv_fwd_common(const Plan& p, const float* x, const float* R, float* out, float* xhat_save,
+                    void* ws, fno::Epilogue ep, hipStream_t s) {
+  int rc = build_tables(p, ws, s);
+  if (rc != FNO_OK) return rc;
+  float2* xh = xhat_save != nullptr ? reinterpret_cast<float2*>(xhat_save) : at<float2>(ws, p.off_s1);
+  rc = forward_chain(p, ws, x, p.Ci, xh, s);
+  if (rc != FNO_OK) return rc;
+  float2* yh = at<float2>(ws, p.off_s2);
+  FNO_HIP(fno::launch_mix_fwd(xh, reinterpret_cast<const float2*>(R), yh, p.B, p.Ci, p.Co, p.K, p.mt,
+                              p.Nt, 1.0 / double(p.Npts), s));
+  return inverse_chain(p, ws, yh, p.Co, out, ep, s);
+}
+
+// shared by the two backward calls; gz is dL/d(pre-activation) [B][Co][grid]
+int conv_bwd_common(const Plan& p, const float* x, const float* xhat_saved, const float* R,
+                    const float* gz, float* gx, float* gR, void* ws, fno::Epilogue ep, hipStream_t s) {
+  int rc;
+  const float2* xh = reinterpret_cast<const float2*>(xhat_saved);
+  if (gR != nullptr && xh == nullptr) {
+    float2* s3 = at<float2>(ws, p.off_s3);
+    rc = forward_chain(p, ws, x, p.Ci, s3, s);
+    if (rc != FNO_OK) return rc;
+    xh = s3;
+  }
+  if (xh == nullptr) xh = at<float2>(ws, p.off_s3);   // unread when gR is null
+  float2* gh = at<float2>(ws, p.off_s1);
+  rc = forward_chain(p, ws, gz, p.Co, gh, s);
+  if (rc != FNO_OK) return rc;
+  float2* gxh = gx != nullptr ? at<float2>(ws, p.off_s2) : nullptr;
+  FNO_HIP(fno::launch_mix_bwd(xh, reinterpret_cast<const float2*>(R), gh,
+                              reinterpret_cast<float2*>(gR), gxh, p.B, p.Ci, p.Co, p.K, p.mt, p.Nt,
+                              1.0 / double(p.Npts), s));
+  if (gx != nullptr) return inverse_chain(p, ws, gxh, p.Ci, gx, ep, s);
+  return FNO_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+int fno_workspace_bytes(const fno_desc* desc, int op, size_t* bytes) {
+  if (bytes == nullptr) { set_detail("bytes is null"); return FNO_EINVAL; }
+  if (op < FNO_OP_SPECTRAL_CONV_FWD || op > FNO_OP_BLOCK_BWD) { set_detail("unknown op"); return FNO_EINVAL; }
+  Plan p;
+  const bool blk = (op == FNO_OP_BLOCK_FWD || op == FNO_OP_BLOCK_BWD);
+  const int rc = make_plan(desc, blk, op == FNO_OP_BLOCK_BWD, &p);
+  if (rc != FNO_OK) return rc;
+  *bytes = p.total;
+  return FNO_OK;
+}
+
+int fno_mode_indices(const fno_desc* desc, int axis, int32_t* out_k, int32_t* out_n) {
+  if (out_n == nullptr) { set_detail("out_n is null"); return FNO_EINVAL; }
+  if (axis < 0 || axis > 3) { set_detail("axis must be 0..3"); return FNO_EINVAL; }
+  Plan p;
+  const int rc = make_plan(desc, false, false, &p);
+  if (rc != FNO_OK && rc != FNO_EUNSUPPORTED) return rc;
+  const int L = p.L[axis], np = p.npos[axis];
+  *out_n = L;
+  if (out_k != nullptr)
+    for (int j = 0; j < L; ++j) out_k[j] = j < np ? j : j - L;
+  return FNO_OK;
+}
+
+int fno_spectral_conv_fwd(const fno_desc* desc, const float* x, const float* R, float* y,
+                          float* xhat_save, void* ws, size_t ws_bytes, void* stream) {
+  Plan p;
+  int rc = make_plan(desc, false, false, &p);
+  if (rc != FNO_OK) return rc;
+  if (x == nullptr || R == nullptr || y == nullptr) { set_detail("x, R and y are required"); return FNO_EINVAL; }
+  rc = check_ws(p, ws, ws_bytes);
+  if (rc != FNO_OK) return rc;
+  fno::Epilogue ep{nullptr, 0, nullptr, 0, 0, nullptr, nullptr, 0};
+  return conv_fwd_common(p, x, R, y, xhat_save, ws, ep, static_cast<hipStream_t>(stream));
+}
+
+int fno_spectral_conv_bwd(const fno_desc* desc, const float* x, const float* xhat_saved,
+                          const float* R, const float* gy, float* gx, float* gR, void* ws,
+                          size_t ws_bytes, void* stream) {
+  Plan p;
+  int rc = make_plan(desc, false, false, &p);
+  if (rc != FNO_OK) return rc;
+  if (R == nullptr || gy == nullptr) { set_detail("R and gy are required"); return FNO_EINVAL; }
+  if (gR != nullptr && x == nullptr && xhat_saved == nullptr) { set_detail("gR needs x or xhat_saved"); return FNO_EINVAL; }
+  rc = check_ws(p, ws, ws_bytes);
+  if (rc != FNO_OK) return rc;
+  if (gx == nullptr && gR == nullptr) return FNO_OK;
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  rc = build_tables(p, ws, s);
+  if (rc != FNO_OK) return rc;
+  fno::Epilogue ep{nullptr, 0, nullptr, 0, 0, nullptr, nullptr, 0};
+  return conv_bwd_common(p, x, xhat_saved, R, gy, gx, gR, ws, ep, s);
+}
+
+int fno_block_fwd(const fno_desc* desc, const float* x, const float* R, const float* W,
+                  const float* b, float* out, float* z_save, float* xhat_save, void* ws,
+                  size_t ws_bytes, void* stream) {
+  Plan p;
+  int rc = make_plan(desc, true, false, &p);
+  if (rc != FNO_OK) return rc;
+  if (x == nullptr || R == nullptr || W == nullptr || out == nullptr) { set_detail("x, R, W and out are required"); return FNO_EINVAL; }
+  rc = check_ws(p, ws, ws_bytes);
+  if (rc != FNO_OK) return rc;
+  fno::Epilogue ep{x, p.Ci, W, p.Ci, 1, b, z_save, desc->activation};
+  return conv_fwd_common(p, x, R, out, xhat_save, ws, ep, static_cast<hipStream_t>(stream));
+}
+
+int fno_block_bwd(const fno_desc* desc, const float* x, const float* R, const float* W,
+                  const float* z_saved, const float* xhat_saved, const float* gout, float* gx,
+                  float* gR, float* gW, float* gb, void* ws, size_t ws_bytes, void* stream) {
+  Plan p;
+  int rc = make_plan(desc, true, true, &p);
+  if (rc != FNO_OK) return rc;
+  if (x == nullptr || R == nullptr || W == nullptr || z_saved == nullptr || gout == nullptr) {
+    set_detail("x, R, W, z_saved and gout are required");
+    return FNO_EINVAL;
+  }
+  rc = check_ws(p, ws, ws_bytes);
+  if (rc != FNO_OK) return rc;
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  rc = build_tables(p, ws, s);
+  if (rc != FNO_OK) return rc;
+  float* gz = at<float>(ws, p.off_gz);
+  double* part = at<double>(ws, p.off_part);
+  const int mse = (desc->flags & FNO_FLAG_MSE_TARGET) ? 1 : 0;
+  const double mse_scale = 2.0 / (double(p.B) * double(p.Co) * double(p.Npts));
+  FNO_HIP(fno::launch_bwd_pointwise(z_saved, gout, x, gz, part, p.part_blocks, p.B, p.Ci, p.Co,
+                                    p.Npts, desc->activation, mse, mse_scale, s));
+  if (gW != nullptr || gb != nullptr)
+    FNO_HIP(fno::launch_reduce_partials(part, p.part_blocks, p.Co, p.Ci, gW, gb, s));
+  if (gx == nullptr && gR == nullptr) return FNO_OK;
+  // gx = K(R^H) gz + W^T gz : the epilogue applies W transposed to gz, no bias, no activation
+  fno::Epilogue ep{gz, p.Co, W, 1, p.Ci, nullptr, nullptr, 0};
+  return conv_bwd_common(p, x, xhat_saved, R, gz, gx, gR, ws, ep, s);
+}
+
+int fno_pointwise_linear(int32_t batch, int32_t c_in, int32_t c_out, int64_t npoints, const float* x,
+                         const float* W, const float* bias, float* y, void* stream) {
+  if (batch < 1 || c_in < 1 || c_out < 1 || npoints < 0) { set_detail("sizes must be positive"); return FNO_EINVAL; }
+  if (x == nullptr || W == nullptr || y == nullptr) { set_detail("x, W and y are required"); return FNO_EINVAL; }
+  if (c_out > 32 || batch > 65535) { set_detail("pointwise_linear covers c_out <= 32, batch <= 65535"); return FNO_EUNSUPPORTED; }
+  FNO_HIP(fno::launch_pointwise_linear(batch, c_in, c_out, npoints, x, W, bias, y,
+                                       static_cast<hipStream_t>(stream)));
+  return FNO_OK;
+}
+
+int fno_pointwise_mlp2(int32_t batch, int32_t c_in, int32_t hidden, int32_t c_out, int64_t npoints,
+                       const float* x, const float* W1, const float* b1, const float* W2,
+                       const float* b2, float* y, void* stream) {
+  if (batch < 1 || c_in < 1 || hidden < 1 || c_out < 1 || npoints < 0) { set_detail("sizes must be positive"); return FNO_EINVAL; }
+  if (x == nullptr || W1 == nullptr || W2 == nullptr || y == nullptr) { set_detail("x, W1, W2 and y are required"); return FNO_EINVAL; }
+  if (c_in > 32 || c_out > 4 || batch > 65535) { set_detail("pointwise_mlp2 covers c_in <= 32, c_out <= 4, batch <= 65535"); return FNO_EUNSUPPORTED; }
+  FNO_HIP(fno::launch_pointwise_mlp2(batch, c_in, hidden, c_out, npoints, x, W1, b1, W2, b2, y,
+                                     static_cast<hipStream_t>(stream)));
+  return FNO_OK;
+}
+
+const char* fno_status_string(int status) {
+  switch (status) {
+    case FNO_OK: return "ok";
+    case FNO_EINVAL: return g_detail[0] ? g_detail : "invalid argument";
+    case FNO_EUNSUPPORTED: return g_detail[0] ? g_detail : "request outside what the kernels cover";
+    case FNO_ENOSPC: return g_detail[0] ? g_detail : "workspace too small or misaligned";
+    case FNO_EHIP: return g_detail[0] ? g_detail : "HIP runtime error";
+    default: return "unknown status";
+  }
+}
+
+}  // extern "C"

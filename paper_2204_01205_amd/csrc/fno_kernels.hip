@@ -1,0 +1,722 @@
+// HIP kernels of libfno for gfx950 (wave64).  What they compute, in the paper's terms
+// (arXiv 2204.01205): the transform F of eq. (3) restricted to the kept low-frequency modes,
+// applied axis by axis (separability, Sec. 2.3); the per-mode weight multiplication of R_phi;
+// the inverse transform; and the pointwise part of the block update of eq. (2) / Sec. 2.4,
+// sigma(W x + b + K x), fused into the last inverse stage.  The adjoint kernels implement the
+// transposed chain (eq. (7)) and the sum-reductions that are the adjoint of broadcasting W
+// and b (Sec. 2.1).
+//
+// Every axis of length N is split N = P * M: M-point FFTs held in registers (fft_reg.h) over
+// the residue classes n = P*n1 + n2, then a P-term twiddle combine evaluated only at the kept
+// frequencies.  M = 1 degenerates to a dense truncated DFT and covers any axis length.
+#include "fno_kernels.h"
+#include "fft_reg.h"
+
+namespace fno {
+
+namespace {
+
+constexpr int kThreads = 256;
+
+__device__ __forceinline__ int kfreq(int j, int L, int npos) { return j < npos ? j : j - L; }
+__device__ __forceinline__ int posmod(int a, int m) { int r = a % m; return r < 0 ? r + m : r; }
+
+__device__ __forceinline__ float gelu_f(float z) {
+  return 0.5f * z * (1.0f + erff(z * 0.70710678118654752440f));
+}
+__device__ __forceinline__ float gelu_prime_f(float z) {
+  const float cdf = 0.5f * (1.0f + erff(z * 0.70710678118654752440f));
+  const float pdf = 0.39894228040143267794f * expf(-0.5f * z * z);
+  return fmaf(z, pdf, cdf);
+}
+
+// ------------------------------------------------------------------------------------------
+// Twiddle tables (double-precision sincospi, rounded once to float)
+// ------------------------------------------------------------------------------------------
+__global__ void axis_table_kernel(float2* tw, int N, int L, int npos, int P) {
+  const int idx = blockIdx.x * blockDim.x + threadIdx.x;
+  if (idx >= L * P) return;
+  const int j = idx / P, n2 = idx % P;
+  const long long k = kfreq(j, L, npos);
+  long long r = (k * n2) % N;
+  if (r < 0) r += N;
+  double s, c;
+  sincospi(-2.0 * double(r) / double(N), &s, &c);
+  tw[idx] = make_float2(float(c), float(s));
+}
+
+__global__ void t_table_kernel(float2* tw, int Nt, int mt) {
+  const int idx = blockIdx.x * blockDim.x + threadIdx.x;
+  if (idx >= Nt * mt) return;
+  const int kt = idx / Nt, n = idx % Nt;
+  const long long r = ((long long)kt * n) % Nt;
+  double s, c;
+  sincospi(-2.0 * double(r) / double(Nt), &s, &c);
+  tw[idx] = make_float2(float(c), float(s));
+}
+
+// ------------------------------------------------------------------------------------------
+// Forward (t, z): one block transforms `ppb` contiguous (b,c,nx,ny) planes of Nz x Nt reals
+// ------------------------------------------------------------------------------------------
+template <int MZ>
+__global__ __launch_bounds__(kThreads) void tz_fwd_kernel(
+    const float* __restrict__ x, float2* __restrict__ out, const float2* __restrict__ twt,
+    const float2* __restrict__ twz, long long planes, int Nz, int Nt, int Lz, int nposz, int mt,
+    int ppb) {
+  HIP_DYNAMIC_SHARED(float, smem)
+  const int Pz = Nz / MZ;
+  const int sS = Nt + 1;                       // row stride of S in floats
+  const int sT = Nz + 1;                       // row stride of T in float2
+  float* S = smem;                             // [ppb][Nz][sS]
+  int s_floats = ppb * Nz * sS;
+  s_floats += (s_floats & 1);
+  float2* T = reinterpret_cast<float2*>(smem + s_floats);   // [ppb][mt][sT]
+  const int tid = threadIdx.x;
+  const long long plane0 = (long long)blockIdx.x * ppb;
+  const int np = (int)min((long long)ppb, planes - plane0);
+  const int plane_elems = Nz * Nt;
+
+  // 1. coalesced load of the planes
+  const float* src = x + plane0 * plane_elems;
+  for (int idx = tid; idx < np * plane_elems; idx += kThreads) {
+    const int row = idx / Nt, t = idx - row * Nt;
+    S[row * sS + t] = src[idx];
+  }
+  __syncthreads();
+
+  // 2. real-to-complex transform over t, kept bins only: one thread per z-row
+  for (int row = tid; row < np * Nz; row += kThreads) {
+    const int p = row / Nz, z = row - p * Nz;
+    const float* srow = S + row * sS;
+    for (int kt0 = 0; kt0 < mt; kt0 += 4) {
+      float2 acc[4];
+#pragma unroll
+      for (int u = 0; u < 4; ++u) acc[u] = make_float2(0.f, 0.f);
+      for (int n = 0; n < Nt; ++n) {
+        const float v = srow[n];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+          if (kt0 + u < mt) {
+            const float2 w = twt[(kt0 + u) * Nt + n];
+            acc[u].x = fmaf(v, w.x, acc[u].x);
+            acc[u].y = fmaf(v, w.y, acc[u].y);
+          }
+        }
+      }
+#pragma unroll
+      for (int u = 0; u < 4; ++u)
+        if (kt0 + u < mt) T[(p * mt + kt0 + u) * sT + z] = acc[u];
+    }
+  }
+  __syncthreads();
+
+  // 3. MZ-point FFTs over the residue classes of z, in place
+  if constexpr (MZ > 1) {
+    for (int idx = tid; idx < np * mt * Pz; idx += kThreads) {
+      const int n2 = idx % Pz, col = idx / Pz;          // col = p*mt + kt
+      float2* base = T + col * sT + n2;
+      float2 a[MZ];
+#pragma unroll
+      for (int n1 = 0; n1 < MZ; ++n1) a[n1] = base[Pz * n1];
+      fft_reg<MZ, -1>(a);
+#pragma unroll
+      for (int m = 0; m < MZ; ++m) base[Pz * m] = a[bitrev<MZ>(m)];
+    }
+    __syncthreads();
+  }
+
+  // 4. twiddle combine at the kept z-frequencies
+  for (int idx = tid; idx < np * Lz * mt; idx += kThreads) {
+    const int kt = idx % mt;
+    const int jz = (idx / mt) % Lz;
+    const int p = idx / (mt * Lz);
+    const int mj = posmod(kfreq(jz, Lz, nposz), MZ);
+    const float2* base = T + (p * mt + kt) * sT + Pz * mj;
+    const float2* w = twz + jz * Pz;
+    float2 acc = make_float2(0.f, 0.f);
+    for (int n2 = 0; n2 < Pz; ++n2) acc = cfma(w[n2], base[n2], acc);
+    out[((plane0 + p) * Lz + jz) * mt + kt] = acc;
+  }
+}
+
+// ------------------------------------------------------------------------------------------
+// Complex pruned transform along the middle axis of [outer][N][inner] -> [outer][L][inner]
+// ------------------------------------------------------------------------------------------
+template <int M>
+__global__ __launch_bounds__(kThreads) void axis_fwd_kernel(
+    const float2* __restrict__ in, float2* __restrict__ out, const float2* __restrict__ tw, int N,
+    int L, int npos, long long inner, int W, int ncb) {
+  HIP_DYNAMIC_SHARED(float, smem)
+  float2* F = reinterpret_cast<float2*>(smem);          // [N][W]
+  const int P = N / M;
+  const int tid = threadIdx.x;
+  const long long o = blockIdx.x / ncb;
+  const long long c0 = (long long)(blockIdx.x % ncb) * W;
+  const int wc = (int)min((long long)W, inner - c0);
+
+  for (int idx = tid; idx < P * W; idx += kThreads) {
+    const int col = idx % W, n2 = idx / W;
+    if (col < wc) {
+      const float2* src = in + (o * N + n2) * inner + c0 + col;
+      float2 a[M];
+#pragma unroll
+      for (int n1 = 0; n1 < M; ++n1) a[n1] = src[(long long)(P * n1) * inner];
+      fft_reg<M, -1>(a);
+#pragma unroll
+      for (int m = 0; m < M; ++m) F[(P * m + n2) * W + col] = a[bitrev<M>(m)];
+    }
+  }
+  __syncthreads();
+  for (int idx = tid; idx < L * W; idx += kThreads) {
+    const int col = idx % W, j = idx / W;
+    if (col < wc) {
+      const int mj = posmod(kfreq(j, L, npos), M);
+      const float2* base = F + (P * mj) * W + col;
+      const float2* w = tw + j * P;
+      float2 acc = make_float2(0.f, 0.f);
+      for (int n2 = 0; n2 < P; ++n2) acc = cfma(w[n2], base[n2 * W], acc);
+      out[(o * L + j) * inner + c0 + col] = acc;
+    }
+  }
+}
+
+// [outer][L][inner] (kept frequencies, zero elsewhere) -> [outer][N][inner], exp(+i...)
+template <int M>
+__global__ __launch_bounds__(kThreads) void axis_inv_kernel(
+    const float2* __restrict__ in, float2* __restrict__ out, const float2* __restrict__ tw, int N,
+    int L, int npos, long long inner, int W, int ncb) {
+  HIP_DYNAMIC_SHARED(float, smem)
+  float2* Y = reinterpret_cast<float2*>(smem);          // [L][W]
+  const int P = N / M;
+  const int tid = threadIdx.x;
+  const long long o = blockIdx.x / ncb;
+  const long long c0 = (long long)(blockIdx.x % ncb) * W;
+  const int wc = (int)min((long long)W, inner - c0);
+  const int kmin = npos - L, kmax = npos - 1;
+
+  for (int idx = tid; idx < L * W; idx += kThreads) {
+    const int col = idx % W, j = idx / W;
+    if (col < wc) Y[idx] = in[(o * L + j) * inner + c0 + col];
+  }
+  __syncthreads();
+  for (int idx = tid; idx < P * W; idx += kThreads) {
+    const int col = idx % W, n2 = idx / W;
+    if (col < wc) {
+      float2 g[M];
+#pragma unroll
+      for (int m = 0; m < M; ++m) {
+        float2 acc = make_float2(0.f, 0.f);
+        for (int k = kmin + posmod(m - kmin, M); k <= kmax; k += M) {
+          const int j = k >= 0 ? k : k + L;
+          acc = cfmac(Y[j * W + col], tw[j * P + n2], acc);
+        }
+        g[m] = acc;
+      }
+      fft_reg<M, +1>(g);
+      float2* dst = out + (o * N + n2) * inner + c0 + col;
+#pragma unroll
+      for (int n1 = 0; n1 < M; ++n1) dst[(long long)(P * n1) * inner] = g[bitrev<M>(n1)];
+    }
+  }
+}
+
+// ------------------------------------------------------------------------------------------
+// Per-mode channel mix (the learned weight multiplication inside R_phi)
+// ------------------------------------------------------------------------------------------
+__device__ __forceinline__ float mode_scale(long long k, int mt, int Nt, float invN) {
+  const int kt = (int)(k % mt);
+  const bool single = (kt == 0) || ((Nt % 2 == 0) && (kt == Nt / 2));
+  return single ? invN : 2.0f * invN;
+}
+
+constexpr int kMixB = 4;   // batch entries held per pass
+
+__global__ __launch_bounds__(kThreads) void mix_fwd_kernel(
+    const float2* __restrict__ xh, const float2* __restrict__ R, float2* __restrict__ yh, int B,
+    int Ci, int Co, long long K, int mt, int Nt, float invN) {
+  const long long k = (long long)blockIdx.x * kThreads + threadIdx.x;
+  const int o = blockIdx.y;
+  if (k >= K) return;
+  const float sc = mode_scale(k, mt, Nt, invN);
+  for (int b0 = 0; b0 < B; b0 += kMixB) {
+    float2 acc[kMixB];
+#pragma unroll
+    for (int u = 0; u < kMixB; ++u) acc[u] = make_float2(0.f, 0.f);
+    for (int i = 0; i < Ci; ++i) {
+      const float2 r = R[((long long)i * Co + o) * K + k];
+#pragma unroll
+      for (int u = 0; u < kMixB; ++u)
+        if (b0 + u < B) acc[u] = cfma(xh[((long long)(b0 + u) * Ci + i) * K + k], r, acc[u]);
+    }
+#pragma unroll
+    for (int u = 0; u < kMixB; ++u)
+      if (b0 + u < B)
+        yh[((long long)(b0 + u) * Co + o) * K + k] = make_float2(acc[u].x * sc, acc[u].y * sc);
+  }
+}
+
+__global__ __launch_bounds__(kThreads) void mix_bwd_kernel(
+    const float2* __restrict__ xh, const float2* __restrict__ R, const float2* __restrict__ gh,
+    float2* __restrict__ gR, float2* __restrict__ gxh, int B, int Ci, int Co, long long K, int mt,
+    int Nt, float invN) {
+  const long long k = (long long)blockIdx.x * kThreads + threadIdx.x;
+  const int i = blockIdx.y;
+  if (k >= K) return;
+  const float sc = mode_scale(k, mt, Nt, invN);
+  for (int b0 = 0; b0 < B; b0 += kMixB) {
+    float2 xv[kMixB], gx[kMixB];
+#pragma unroll
+    for (int u = 0; u < kMixB; ++u) {
+      gx[u] = make_float2(0.f, 0.f);
+      xv[u] = (b0 + u < B) ? xh[((long long)(b0 + u) * Ci + i) * K + k] : make_float2(0.f, 0.f);
+    }
+    for (int o = 0; o < Co; ++o) {
+      const long long ridx = ((long long)i * Co + o) * K + k;
+      const float2 r = R[ridx];
+      float2 gr = make_float2(0.f, 0.f);
+      if (gR != nullptr && b0 > 0) gr = gR[ridx];
+#pragma unroll
+      for (int u = 0; u < kMixB; ++u) {
+        if (b0 + u < B) {
+          float2 gy = gh[((long long)(b0 + u) * Co + o) * K + k];
+          gy.x *= sc; gy.y *= sc;
+          gr = cfmac(gy, xv[u], gr);        // conj(xh) * gy
+          gx[u] = cfmac(gy, r, gx[u]);      // conj(R) * gy
+        }
+      }
+      if (gR != nullptr) gR[ridx] = gr;
+    }
+    if (gxh != nullptr) {
+#pragma unroll
+      for (int u = 0; u < kMixB; ++u)
+        if (b0 + u < B) gxh[((long long)(b0 + u) * Ci + i) * K + k] = gx[u];
+    }
+  }
+}
+
+// ------------------------------------------------------------------------------------------
+// Inverse (z, t) with the block epilogue.  One block: all output channels of one (b,nx,ny)
+// column, for the z rows of Q consecutive residue classes (z = Pz*n1 + n2).
+// ------------------------------------------------------------------------------------------
+struct EpiArgs {
+  const float* u; int Cu; const float* W; int w_so, w_si; const float* bias; float* zsave; int act;
+};
+
+template <int MZ, int CO>
+__global__ __launch_bounds__(kThreads) void zt_inv_kernel(
+    const float2* __restrict__ a, float* __restrict__ out, const float2* __restrict__ twt,
+    const float2* __restrict__ twz, int Co, int NxNy, int Nz, int Nt, int Lz, int nposz, int mt,
+    int Q, EpiArgs ep) {
+  HIP_DYNAMIC_SHARED(float, smem)
+  const int Pz = Nz / MZ;
+  const int G = Pz / Q;
+  const int Rz = Q * MZ;
+  const int sY = Nt + 1;
+  float2* V = reinterpret_cast<float2*>(smem);                 // [Co][Rz][mt]
+  float* Y = smem + 2 * Co * Rz * mt;                          // [Co][Rz][sY]
+  const int tid = threadIdx.x;
+  const long long bxy = blockIdx.x / G;
+  const int g = blockIdx.x % G;
+  const long long b = bxy / NxNy;
+  const long long xy = bxy % NxNy;
+  const int kmin = nposz - Lz, kmax = nposz - 1;
+
+  // Z: gather the kept z-frequencies with their twiddle into MZ bins, inverse FFT over n1
+  for (int idx = tid; idx < Co * mt * Q; idx += kThreads) {
+    const int q = idx % Q;
+    const int kt = (idx / Q) % mt;
+    const int o = idx / (Q * mt);
+    const int n2 = g * Q + q;
+    const float2* src = a + (((b * Co + o) * NxNy + xy) * Lz) * mt + kt;
+    float2 gbin[MZ];
+#pragma unroll
+    for (int m = 0; m < MZ; ++m) {
+      float2 acc = make_float2(0.f, 0.f);
+      for (int k = kmin + posmod(m - kmin, MZ); k <= kmax; k += MZ) {
+        const int j = k >= 0 ? k : k + Lz;
+        acc = cfmac(src[j * mt], twz[j * Pz + n2], acc);
+      }
+      gbin[m] = acc;
+    }
+    fft_reg<MZ, +1>(gbin);
+#pragma unroll
+    for (int n1 = 0; n1 < MZ; ++n1) V[((o * Rz) + n1 * Q + q) * mt + kt] = gbin[bitrev<MZ>(n1)];
+  }
+  __syncthreads();
+
+  // T: complex-to-real over t, one thread per (channel, row)
+  for (int idx = tid; idx < Co * Rz; idx += kThreads) {
+    const float2* vrow = V + idx * mt;
+    float* yrow = Y + idx * sY;
+    for (int n0 = 0; n0 < Nt; n0 += 4) {
+      float acc[4] = {0.f, 0.f, 0.f, 0.f};
+      for (int kt = 0; kt < mt; ++kt) {
+        const float2 v = vrow[kt];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+          if (n0 + u < Nt) {
+            const float2 w = twt[kt * Nt + n0 + u];
+            acc[u] = fmaf(v.x, w.x, acc[u]);
+            acc[u] = fmaf(v.y, w.y, acc[u]);
+          }
+        }
+      }
+#pragma unroll
+      for (int u = 0; u < 4; ++u)
+        if (n0 + u < Nt) yrow[n0 + u] = acc[u];
+    }
+  }
+  __syncthreads();
+
+  // E: out = act(ys + W u + bias), one thread per point, all channels
+  const long long Npts = (long long)NxNy * Nz * Nt;
+  for (int idx = tid; idx < Rz * Nt; idx += kThreads) {
+    const int t = idx % Nt, r = idx / Nt;
+    const int z = Pz * (r / Q) + g * Q + (r % Q);
+    const long long off = (xy * Nz + z) * Nt + t;
+    float acc[CO];
+#pragma unroll
+    for (int o = 0; o < CO; ++o) acc[o] = (ep.bias != nullptr && o < Co) ? ep.bias[o] : 0.f;
+    if (ep.u != nullptr) {
+      for (int i = 0; i < ep.Cu; ++i) {
+        const float xv = ep.u[(b * ep.Cu + i) * Npts + off];
+#pragma unroll
+        for (int o = 0; o < CO; ++o)
+          if (o < Co) acc[o] = fmaf(ep.W[o * ep.w_so + i * ep.w_si], xv, acc[o]);
+      }
+    }
+#pragma unroll
+    for (int o = 0; o < CO; ++o) {
+      if (o < Co) {
+        const float zv = acc[o] + Y[(o * Rz + r) * sY + t];
+        const long long oidx = (b * Co + o) * Npts + off;
+        if (ep.zsave != nullptr) ep.zsave[oidx] = zv;
+        out[oidx] = ep.act ? gelu_f(zv) : zv;
+      }
+    }
+  }
+}
+
+// ------------------------------------------------------------------------------------------
+// Backward pointwise: gz = g * act'(z); partial sums for gb and gW
+// ------------------------------------------------------------------------------------------
+constexpr int kBwdTile = 256;      // points per tile (= threads)
+
+__global__ __launch_bounds__(kThreads) void bwd_pointwise_kernel(
+    const float* __restrict__ z, const float* __restrict__ gout, const float* __restrict__ x,
+    float* __restrict__ gz_out, double* __restrict__ part, int B, int Ci, int Co, long long N,
+    int act, int mse_target, float mse_scale) {
+  HIP_DYNAMIC_SHARED(float, smem)
+  const int sR = kBwdTile + 1;
+  float* Gs = smem;                 // [Co][sR]
+  float* Xs = smem + Co * sR;       // [Ci][sR]
+  const int tid = threadIdx.x;
+  const long long tiles_per_b = (N + kBwdTile - 1) / kBwdTile;
+  const long long ntiles = tiles_per_b * B;
+  const int npairs = Co * Ci + Co;
+  // each thread owns up to 2 of the Co*Ci + Co sums (npairs <= 2 * kThreads is checked on the host)
+  double acc0 = 0.0, acc1 = 0.0;
+  for (long long tile = blockIdx.x; tile < ntiles; tile += gridDim.x) {
+    const long long b = tile / tiles_per_b;
+    const long long p = (tile % tiles_per_b) * kBwdTile + tid;
+    const bool live = p < N;
+    for (int o = 0; o < Co; ++o) {
+      float gv = 0.f;
+      if (live) {
+        const long long e = (b * Co + o) * N + p;
+        const float zv = z[e];
+        float g = gout[e];
+        if (mse_target) g = mse_scale * ((act ? gelu_f(zv) : zv) - g);
+        gv = act ? g * gelu_prime_f(zv) : g;
+        gz_out[e] = gv;
+      }
+      Gs[o * sR + tid] = gv;
+    }
+    for (int i = 0; i < Ci; ++i) Xs[i * sR + tid] = live ? x[(b * Ci + i) * N + p] : 0.f;
+    __syncthreads();
+#pragma unroll
+    for (int h = 0; h < 2; ++h) {
+      const int q = tid + h * kThreads;
+      if (q < npairs) {
+        float s = 0.f;
+        if (q < Co * Ci) {
+          const float* gr = Gs + (q / Ci) * sR;
+          const float* xr = Xs + (q % Ci) * sR;
+          for (int t = 0; t < kBwdTile; ++t) s = fmaf(gr[t], xr[t], s);
+        } else {
+          const float* gr = Gs + (q - Co * Ci) * sR;
+          for (int t = 0; t < kBwdTile; ++t) s += gr[t];
+        }
+        if (h == 0) acc0 += double(s); else acc1 += double(s);
+      }
+    }
+    __syncthreads();
+  }
+  if (tid < npairs) part[(long long)blockIdx.x * npairs + tid] = acc0;
+  if (tid + kThreads < npairs) part[(long long)blockIdx.x * npairs + tid + kThreads] = acc1;
+}
+
+__global__ void reduce_partials_kernel(const double* __restrict__ part, int nblk, int Co, int Ci,
+                                       float* __restrict__ gW, float* __restrict__ gb) {
+  const int q = blockIdx.x * blockDim.x + threadIdx.x;
+  const int npairs = Co * Ci + Co;
+  if (q >= npairs) return;
+  double s = 0.0;
+  for (int blk = 0; blk < nblk; ++blk) s += part[(long long)blk * npairs + q];
+  if (q < Co * Ci) { if (gW != nullptr) gW[q] = float(s); }
+  else if (gb != nullptr) gb[q - Co * Ci] = float(s);
+}
+
+// ------------------------------------------------------------------------------------------
+// Pointwise lift and projection (Sec. 2.4)
+// ------------------------------------------------------------------------------------------
+template <int CO>
+__global__ __launch_bounds__(kThreads) void pointwise_linear_kernel(
+    int Ci, int Co, long long np, const float* __restrict__ x, const float* __restrict__ W,
+    const float* __restrict__ bias, float* __restrict__ y) {
+  const long long p = (long long)blockIdx.x * kThreads + threadIdx.x;
+  const long long b = blockIdx.y;
+  if (p >= np) return;
+  float acc[CO];
+#pragma unroll
+  for (int o = 0; o < CO; ++o) acc[o] = (bias != nullptr && o < Co) ? bias[o] : 0.f;
+  for (int i = 0; i < Ci; ++i) {
+    const float xv = x[(b * Ci + i) * np + p];
+#pragma unroll
+    for (int o = 0; o < CO; ++o)
+      if (o < Co) acc[o] = fmaf(W[o * Ci + i], xv, acc[o]);
+  }
+#pragma unroll
+  for (int o = 0; o < CO; ++o)
+    if (o < Co) y[(b * Co + o) * np + p] = acc[o];
+}
+
+template <int CI>
+__global__ __launch_bounds__(kThreads) void pointwise_mlp2_kernel(
+    int Ci, int H, int Co, long long np, const float* __restrict__ x, const float* __restrict__ W1,
+    const float* __restrict__ b1, const float* __restrict__ W2, const float* __restrict__ b2,
+    float* __restrict__ y) {
+  const long long p = (long long)blockIdx.x * kThreads + threadIdx.x;
+  const long long b = blockIdx.y;
+  if (p >= np) return;
+  float xv[CI];
+#pragma unroll
+  for (int i = 0; i < CI; ++i) xv[i] = (i < Ci) ? x[(b * Ci + i) * np + p] : 0.f;
+  float acc[4];
+#pragma unroll
+  for (int o = 0; o < 4; ++o) acc[o] = (b2 != nullptr && o < Co) ? b2[o] : 0.f;
+  for (int h = 0; h < H; ++h) {
+    float s = (b1 != nullptr) ? b1[h] : 0.f;
+#pragma unroll
+    for (int i = 0; i < CI; ++i)
+      if (i < Ci) s = fmaf(W1[h * Ci + i], xv[i], s);
+    const float gh = gelu_f(s);
+#pragma unroll
+    for (int o = 0; o < 4; ++o)
+      if (o < Co) acc[o] = fmaf(W2[o * H + h], gh, acc[o]);
+  }
+#pragma unroll
+  for (int o = 0; o < 4; ++o)
+    if (o < Co) y[(b * Co + o) * np + p] = acc[o];
+}
+
+int pick_q(AxisPlan az, int Nt) {
+  // smallest divisor Q of Pz whose Q adjacent rows span at least 128 bytes
+  for (int q = 1; q <= az.P; ++q)
+    if (az.P % q == 0 && q * Nt >= 32) return q;
+  return az.P;
+}
+
+size_t tz_fwd_lds(AxisPlan az, int Nt, int mt, int ppb) {
+  size_t s_floats = (size_t)ppb * az.N * (Nt + 1);
+  s_floats += (s_floats & 1);
+  return s_floats * 4 + (size_t)ppb * mt * (az.N + 1) * 8;
+}
+
+size_t zt_inv_lds(AxisPlan az, int Nt, int mt, int Co) {
+  const int Rz = pick_q(az, Nt) * az.M;
+  return (size_t)Co * Rz * ((size_t)mt * 8 + (size_t)(Nt + 1) * 4);
+}
+
+int axis_cols(AxisPlan ax, int64_t inner) {
+  int w = 16;
+  while (w > 1 && (size_t)ax.N * w * 8 > (size_t)kLdsBudget) w >>= 1;
+  while (w > 1 && (w >> 1) >= inner) w >>= 1;
+  return w;
+}
+
+#define FNO_DISPATCH_M(Mval, CALL)                \
+  switch (Mval) {                                 \
+    case 1: { constexpr int MM = 1; CALL; } break;   \
+    case 2: { constexpr int MM = 2; CALL; } break;   \
+    case 4: { constexpr int MM = 4; CALL; } break;   \
+    case 8: { constexpr int MM = 8; CALL; } break;   \
+    case 16: { constexpr int MM = 16; CALL; } break; \
+    case 32: { constexpr int MM = 32; CALL; } break; \
+    default: return hipErrorInvalidValue;         \
+  }
+
+}  // namespace
+
+bool tz_fwd_fits(AxisPlan az, int Nt, int mt) { return tz_fwd_lds(az, Nt, mt, 1) <= (size_t)kLdsBudget; }
+bool zt_inv_fits(AxisPlan az, int Nt, int mt, int Co) {
+  return Co <= kMaxCo && zt_inv_lds(az, Nt, mt, Co) <= (size_t)(64 * 1024);
+}
+bool axis_fits(AxisPlan ax) { return (size_t)ax.N * 8 <= (size_t)kLdsBudget; }
+
+hipError_t launch_axis_table(float2* tw, AxisPlan ax, hipStream_t s) {
+  const int n = ax.L * ax.P;
+  hipLaunchKernelGGL(axis_table_kernel, dim3((n + 255) / 256), dim3(256), 0, s, tw, ax.N, ax.L,
+                     ax.npos, ax.P);
+  return hipGetLastError();
+}
+
+hipError_t launch_t_table(float2* twt, int Nt, int mt, hipStream_t s) {
+  const int n = Nt * mt;
+  hipLaunchKernelGGL(t_table_kernel, dim3((n + 255) / 256), dim3(256), 0, s, twt, Nt, mt);
+  return hipGetLastError();
+}
+
+hipError_t launch_tz_fwd(const float* x, float2* out, const float2* twt, const float2* twz,
+                         int64_t planes, AxisPlan az, int Nt, int mt, hipStream_t s) {
+  if (planes <= 0) return hipSuccess;
+  int ppb = 1;
+  // enough rows to occupy the block, within an LDS share that keeps several blocks per CU
+  
+  while (ppb * 2 * az.N <= 2 * kThreads && tz_fwd_lds(az, Nt, mt, ppb * 2) <= (size_t)(32 * 1024)) ppb *= 2;
+  const size_t lds = tz_fwd_lds(az, Nt, mt, ppb);
+  const int64_t nblk = (planes + ppb - 1) / ppb;
+  if (nblk > 0x7fffffffLL) return hipErrorInvalidValue;
+  FNO_DISPATCH_M(az.M, hipLaunchKernelGGL((tz_fwd_kernel<MM>), dim3((unsigned)nblk), dim3(kThreads),
+                                          lds, s, x, out, twt, twz, (long long)planes, az.N, Nt,
+                                          az.L, az.npos, mt, ppb));
+  return hipGetLastError();
+}
+
+hipError_t launch_axis_fwd(const float2* in, float2* out, const float2* tw, int64_t outer,
+                           AxisPlan ax, int64_t inner, hipStream_t s) {
+  if (outer <= 0 || inner <= 0) return hipSuccess;
+  const int W = axis_cols(ax, inner);
+  const int64_t ncb = (inner + W - 1) / W;
+  const int64_t nblk = outer * ncb;
+  if (nblk > 0x7fffffffLL || ncb > 0x7fffffffLL) return hipErrorInvalidValue;
+  const size_t lds = (size_t)ax.N * W * 8;
+  FNO_DISPATCH_M(ax.M, hipLaunchKernelGGL((axis_fwd_kernel<MM>), dim3((unsigned)nblk),
+                                          dim3(kThreads), lds, s, in, out, tw, ax.N, ax.L, ax.npos,
+                                          (long long)inner, W, (int)ncb));
+  return hipGetLastError();
+}
+
+hipError_t launch_axis_inv(const float2* in, float2* out, const float2* tw, int64_t outer,
+                           AxisPlan ax, int64_t inner, hipStream_t s) {
+  if (outer <= 0 || inner <= 0) return hipSuccess;
+  const int W = axis_cols(ax, inner);
+  const int64_t ncb = (inner + W - 1) / W;
+  const int64_t nblk = outer * ncb;
+  if (nblk > 0x7fffffffLL || ncb > 0x7fffffffLL) return hipErrorInvalidValue;
+  const size_t lds = (size_t)ax.L * W * 8;
+  FNO_DISPATCH_M(ax.M, hipLaunchKernelGGL((axis_inv_kernel<MM>), dim3((unsigned)nblk),
+                                          dim3(kThreads), lds, s, in, out, tw, ax.N, ax.L, ax.npos,
+                                          (long long)inner, W, (int)ncb));
+  return hipGetLastError();
+}
+
+hipError_t launch_mix_fwd(const float2* xh, const float2* R, float2* yh, int B, int Ci, int Co,
+                          int64_t K, int mt, int Nt, double invN, hipStream_t s) {
+  const int64_t nb = (K + kThreads - 1) / kThreads;
+  if (nb > 0x7fffffffLL || Co > 65535) return hipErrorInvalidValue;
+  hipLaunchKernelGGL(mix_fwd_kernel, dim3((unsigned)nb, (unsigned)Co), dim3(kThreads), 0, s, xh, R,
+                     yh, B, Ci, Co, (long long)K, mt, Nt, (float)invN);
+  return hipGetLastError();
+}
+
+hipError_t launch_mix_bwd(const float2* xh, const float2* R, const float2* gh, float2* gR,
+                          float2* gxh, int B, int Ci, int Co, int64_t K, int mt, int Nt,
+                          double invN, hipStream_t s) {
+  const int64_t nb = (K + kThreads - 1) / kThreads;
+  if (nb > 0x7fffffffLL || Ci > 65535) return hipErrorInvalidValue;
+  hipLaunchKernelGGL(mix_bwd_kernel, dim3((unsigned)nb, (unsigned)Ci), dim3(kThreads), 0, s, xh, R,
+                     gh, gR, gxh, B, Ci, Co, (long long)K, mt, Nt, (float)invN);
+  return hipGetLastError();
+}
+
+hipError_t launch_zt_inv(const float2* a, float* out, const float2* twt, const float2* twz, int B,
+                         int Co, int Nx, int Ny, AxisPlan az, int Nt, int mt, Epilogue ep,
+                         hipStream_t s) {
+  const int Q = pick_q(az, Nt);
+  const int G = az.P / Q;
+  const int64_t nblk = (int64_t)B * Nx * Ny * G;
+  if (nblk <= 0) return hipSuccess;
+  if (nblk > 0x7fffffffLL || Co > kMaxCo) return hipErrorInvalidValue;
+  const size_t lds = zt_inv_lds(az, Nt, mt, Co);
+  EpiArgs e{ep.u, ep.Cu, ep.W, ep.w_so, ep.w_si, ep.bias, ep.zsave, ep.act};
+  const int NxNy = Nx * Ny;
+#define FNO_ZT_CALL(COV)                                                                          \
+  FNO_DISPATCH_M(az.M, hipLaunchKernelGGL((zt_inv_kernel<MM, COV>), dim3((unsigned)nblk),         \
+                                          dim3(kThreads), lds, s, a, out, twt, twz, Co, NxNy,     \
+                                          az.N, Nt, az.L, az.npos, mt, Q, e))
+  if (Co <= 8) { FNO_ZT_CALL(8); }
+  else if (Co <= 20) { FNO_ZT_CALL(20); }
+  else { FNO_ZT_CALL(32); }
+#undef FNO_ZT_CALL
+  return hipGetLastError();
+}
+
+int bwd_pointwise_blocks(int B, int64_t N) {
+  const int64_t tiles = (int64_t)B * ((N + kBwdTile - 1) / kBwdTile);
+  return (int)(tiles < 2048 ? tiles : 2048);
+}
+
+hipError_t launch_bwd_pointwise(const float* z, const float* gout, const float* x, float* gz_out,
+                                double* part, int nblk, int B, int Ci, int Co, int64_t N, int act,
+                                int mse_target, double mse_scale, hipStream_t s) {
+  if (Co * Ci + Co > 2 * kThreads) return hipErrorInvalidValue;
+  const size_t lds = (size_t)(Co + Ci) * (kBwdTile + 1) * 4;
+  hipLaunchKernelGGL(bwd_pointwise_kernel, dim3((unsigned)nblk), dim3(kThreads), lds, s, z, gout,
+                     x, gz_out, part, B, Ci, Co, (long long)N, act, mse_target, (float)mse_scale);
+  return hipGetLastError();
+}
+
+hipError_t launch_reduce_partials(const double* part, int nblk, int Co, int Ci, float* gW,
+                                  float* gb, hipStream_t s) {
+  const int npairs = Co * Ci + Co;
+  hipLaunchKernelGGL(reduce_partials_kernel, dim3((npairs + 63) / 64), dim3(64), 0, s, part, nblk,
+                     Co, Ci, gW, gb);
+  return hipGetLastError();
+}
+
+hipError_t launch_pointwise_linear(int B, int Ci, int Co, int64_t np, const float* x, const float* W,
+                                   const float* bias, float* y, hipStream_t s) {
+  const int64_t nb = (np + kThreads - 1) / kThreads;
+  if (nb > 0x7fffffffLL || B > 65535 || Co > 32) return hipErrorInvalidValue;
+  if (nb == 0 || B == 0) return hipSuccess;
+  dim3 grid((unsigned)nb, (unsigned)B);
+  if (Co <= 8)
+    hipLaunchKernelGGL((pointwise_linear_kernel<8>), grid, dim3(kThreads), 0, s, Ci, Co,
+                       (long long)np, x, W, bias, y);
+  else if (Co <= 20)
+    hipLaunchKernelGGL((pointwise_linear_kernel<20>), grid, dim3(kThreads), 0, s, Ci, Co,
+                       (long long)np, x, W, bias, y);
+  else
+    hipLaunchKernelGGL((pointwise_linear_kernel<32>), grid, dim3(kThreads), 0, s, Ci, Co,
+                       (long long)np, x, W, bias, y);
+  return hipGetLastError();
+}
+
+hipError_t launch_pointwise_mlp2(int B, int Ci, int H, int Co, int64_t np, const float* x,
+                                 const float* W1, const float* b1, const float* W2,
+                                 const float* b2, float* y, hipStream_t s) {
+  const int64_t nb = (np + kThreads - 1) / kThreads;
+  if (nb > 0x7fffffffLL || B > 65535 || Co > 4 || Ci > 32) return hipErrorInvalidValue;
+  if (nb == 0 || B == 0) return hipSuccess;
+  dim3 grid((unsigned)nb, (unsigned)B);
+  if (Ci <= 20)
+    hipLaunchKernelGGL((pointwise_mlp2_kernel<20>), grid, dim3(kThreads), 0, s, Ci, H, Co,
+                       (long long)np, x, W1, b1, W2, b2, y);
+  else
+    hipLaunchKernelGGL((pointwise_mlp2_kernel<32>), grid, dim3(kThreads), 0, s, Ci, H, Co,
+                       (long long)np, x, W1, b1, W2, b2, y);
+  return hipGetLastError();
+}
+
+}  // namespace fno
