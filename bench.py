@@ -1,0 +1,160 @@
+"""Benchmark of the FNO block on one MI355X.
+
+A step is one pass of the whole hot path (fno_block_fwd through the C ABI: forward pruned
+transforms, mode mix, inverse transforms, fused W x + b + GELU epilogue) over one batch of
+synthetic input resident in HBM.  Prints ONE JSON line with the throughput in
+Gpoint-channels/s, the roofline of the dominant kernel (timed live with HIP events on the
+launch stream) and the float64 CPU oracle timed on a bounded sample as a baseline.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=10)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--config", default="cfg4", help="workload name from synth.CONFIGS (block forward)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--traffic-file", default=os.path.join(ROOT, "profiles", "traffic.json"),
+                    help="measured HBM bytes per launch of the dominant kernel (from rocprofv3 --pmc)")
+    return ap.parse_args()
+
+
+def cpu_baseline(cfg):
+    """The oracle as it stands on a bounded sample: a width-1 block on a 64-wide x-slice."""
+    import numpy as np
+    from oracle import fno_oracle as O
+    from paper_2204_01205_amd import synth
+    try:
+        from threadpoolctl import threadpool_info
+        threads = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
+    except Exception:
+        threads = len(os.sched_getaffinity(0))
+    nx, ny, nz, nt = cfg["grid"]
+    mx = cfg["modes"][0]
+    sx = min(nx, max(64, 2 * mx))
+    while sx < 2 * mx:
+        sx *= 2
+    grid = (sx, ny, nz, nt)
+    spec = O.LayerSpec(grid, tuple(cfg["modes"]), 0)
+    counts = synth.retained_counts(cfg["modes"])
+    x = synth.normal_field(0, synth.T_X, 1, 1, grid)
+    R = synth.spectral_weights(0, 1, 1, counts)
+    W = synth.linear_weights(0, 1, 1)
+    b = synth.bias(0, 1)
+    t0 = time.perf_counter()
+    O.block_fwd(x, R, W, b, spec)
+    dt = time.perf_counter() - t0
+    pc = float(np.prod(grid))
+    return {"value": pc / dt / 1e9, "unit": "Gpoint-channels/s", "cores": int(threads), "kind": "oracle",
+            "sample": f"float64 oracle block_fwd, width 1, grid {grid[0]}x{grid[1]}x{grid[2]}x{grid[3]} "
+                      f"(an x-slice of one channel slab), modes as the workload; {dt:.1f} s",
+            "host_cores_visible": len(os.sched_getaffinity(0))}
+
+
+def main():
+    args = parse()
+    if args.gpus != 1:
+        print("bench.py: this build covers one GPU's share of the work only; run with --gpus 1 "
+              "(no collectives or sharding are built)", file=sys.stderr)
+        sys.exit(2)
+    import torch
+    from paper_2204_01205_amd import binding as B
+    from paper_2204_01205_amd import synth
+
+    cfg = synth.CONFIGS[args.config]
+    batch, width, grid, modes = cfg["batch"], cfg["width"], tuple(cfg["grid"]), tuple(cfg["modes"])
+    counts = synth.retained_counts(modes)
+    npts = 1
+    for n in grid:
+        npts *= n
+    pc = batch * width * npts
+    nmodes = counts[0] * counts[1] * counts[2] * counts[3]
+
+    torch.cuda.set_device(0)
+    gen = torch.Generator(device="cuda")
+    gen.manual_seed(0)
+    x = torch.randn((batch, width) + grid, device="cuda", generator=gen)
+    R = torch.view_as_complex(torch.randn((width, width) + counts + (2,), device="cuda", generator=gen)
+                              / float(width))
+    W = torch.randn((width, width), device="cuda", generator=gen) / float(width) ** 0.5
+    b = 0.1 * torch.randn((width,), device="cuda", generator=gen)
+    out = torch.empty_like(x)
+    desc = B.make_desc(batch, width, width, grid, modes, 0, B.FNO_ACT_GELU)
+    ws = B.alloc_workspace(desc, B.FNO_OP_BLOCK_FWD)
+
+    def step():
+        B.fno_block_fwd(desc, x, R, W, b, out, None, None, ws)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    B.fno_timing_enable(True)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    records = B.fno_timing_read()
+    B.fno_timing_enable(False)
+
+    ms_per_step = 1e3 * dt / args.steps
+    stage_ms = {}
+    for name, ms in records:
+        stage_ms.setdefault(name, []).append(ms)
+    stage_avg = {k: sum(v) / len(v) for k, v in stage_ms.items()}
+    dominant = max(stage_avg, key=stage_avg.get)
+    # algorithmic bytes per launch of each full-grid sweep: 4 B per point-channel per tensor touched
+    alg_bytes = {"zt_inv": 8.0 * pc,      # reads x for W x, writes out (pruned spectrum not counted)
+                 "tz_fwd": 4.0 * pc}      # reads x
+    dom_bytes = alg_bytes.get(dominant, 0.0)
+    achieved = dom_bytes / (stage_avg[dominant] * 1e-3) / 1e9
+    traffic = None
+    if os.path.exists(args.traffic_file):
+        try:
+            tf = json.load(open(args.traffic_file))
+            ent = tf.get(args.config, {}).get(dominant)
+            if ent is not None:
+                traffic = ent
+        except Exception:
+            traffic = None
+    whole_bytes = 12.0 * pc + 8.0 * width * width * nmodes
+    line = {
+        "metric": "FNO spectral layer Gpoint-channels/s + achieved HBM GB/s on 1 MI355X",
+        "value": pc / (ms_per_step * 1e-3) / 1e9,
+        "unit": "Gpoint-channels/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f32", "data": "synthetic",
+        "config": {"workload": f"{args.config}: fno_block_fwd, batch {batch}, width {width}, grid "
+                               f"{grid[0]}x{grid[1]}x{grid[2]}x{grid[3]}, kept modes {counts[0]}x{counts[1]}x{counts[2]}x{counts[3]}",
+                   "global_batch": batch, "parallelism": "single GPU"},
+        "whole_path": {"algorithmic_GB": whole_bytes / 1e9,
+                       "achieved_GBps": whole_bytes / (ms_per_step * 1e-3) / 1e9,
+                       "frac_of_hbm_peak": whole_bytes / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS},
+        "roofline": {"kernel": dominant, "bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS,
+                     "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS, "traffic": traffic,
+                     "avg_launch_ms": stage_avg[dominant], "algorithmic_bytes_per_launch": dom_bytes},
+        "stage_ms": stage_avg,
+    }
+    if not args.no_cpu_baseline:
+        line["cpu_baseline"] = cpu_baseline(cfg)
+    print(json.dumps(line))
+
+
+if __name__ == "__main__":
+    main()

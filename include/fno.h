@@ -133,6 +133,20 @@ int fno_pointwise_mlp2(int32_t batch, int32_t c_in, int32_t hidden, int32_t c_ou
                        const float* x, const float* W1, const float* b1, const float* W2,
                        const float* b2, float* y, void* stream);
 
+/* Per-stage timing for benchmarks.  While enabled, every library call brackets each kernel it
+ * launches with a pair of HIP events on the call's stream (events are created on first use and
+ * kept).  fno_timing_read waits for the recorded events, returns up to `capacity` records in
+ * launch order (stage id FNO_STAGE_*, elapsed milliseconds; host arrays) and clears the log.
+ * This log is the library's only process-wide state and is not thread-safe; leave it disabled
+ * under graph capture.  At most 8192 records are kept between reads. */
+enum {
+  FNO_STAGE_TZ_FWD = 0, FNO_STAGE_Y_FWD = 1, FNO_STAGE_X_FWD = 2, FNO_STAGE_MIX = 3,
+  FNO_STAGE_X_INV = 4, FNO_STAGE_Y_INV = 5, FNO_STAGE_ZT_INV = 6, FNO_STAGE_MIX_BWD = 7,
+  FNO_STAGE_BWD_POINTWISE = 8
+};
+int fno_timing_enable(int on);
+int fno_timing_read(int32_t* stages, float* ms, int32_t capacity, int32_t* count);
+
 /* Text for a status code; for FNO_EHIP / FNO_EUNSUPPORTED the calling thread's last detail. */
 const char* fno_status_string(int status);
 

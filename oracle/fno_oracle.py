@@ -41,7 +41,12 @@ from dataclasses import dataclass
 from typing import Sequence
 
 import numpy as np
-from scipy.special import erf as _erf
+import torch
+
+
+def _erf(v: np.ndarray) -> np.ndarray:
+    """erf in float64 (PyTorch's CPU routine: same values as scipy's to 1 ulp, multi-threaded)."""
+    return torch.erf(torch.from_numpy(np.ascontiguousarray(v, dtype=np.float64))).numpy()
 
 __all__ = [
     "LayerSpec", "spatial_modes", "temporal_modes", "mode_lists", "hermitian_weights",
@@ -49,7 +54,7 @@ __all__ = [
     "spectral_conv_fwd", "spectral_conv_bwd", "channel_affine", "gelu", "gelu_prime",
     "block_fwd", "block_bwd", "mse_loss", "mse_grad",
     "brute_forward_spectrum", "brute_inverse_spectrum", "brute_spectral_conv",
-    "separable_forward_spectrum", "inverse_at_points",
+    "separable_forward_spectrum", "inverse_at_points", "separable_weight_grads",
     "pointwise_linear", "pointwise_mlp2", "fno_forward",
 ]
 
@@ -126,13 +131,16 @@ def dft_matrix(n: int, ks: Sequence[int], sign: float) -> np.ndarray:
 
 
 def _apply_last(a: np.ndarray, m: np.ndarray) -> np.ndarray:
-    """out[..., j] = sum_p a[..., p] * m[j, p]"""
-    return np.matmul(a, m.T)
+    """out[..., j] = sum_p a[..., p] * m[j, p]   (a real or complex, m complex)"""
+    if np.iscomplexobj(a):
+        return np.matmul(a, m.T)
+    mt_ = np.ascontiguousarray(m.T)
+    return np.matmul(a, mt_.real) + 1j * np.matmul(a, mt_.imag)
 
 
 def _apply_axis(a: np.ndarray, m: np.ndarray, axis: int) -> np.ndarray:
-    a = np.moveaxis(a, axis, -1)
-    out = _apply_last(a, m)
+    """Same contraction along another axis: out[.., j, ..] = sum_p a[.., p, ..] * m[j, p]."""
+    out = np.tensordot(a, m, axes=([axis], [1]))      # contracted axis reappears last
     return np.moveaxis(out, -1, axis)
 
 
@@ -147,7 +155,7 @@ def forward_spectrum(x: np.ndarray, spec: LayerSpec) -> np.ndarray:
         raise ValueError("grid mismatch")
     kx, ky, kz, kt = mode_lists(spec)
     nx, ny, nz, nt = spec.grid
-    a = _apply_last(x.astype(np.complex128), dft_matrix(nt, kt, -1.0))
+    a = _apply_last(x, dft_matrix(nt, kt, -1.0))
     a = _apply_axis(a, dft_matrix(nz, kz, -1.0), -2)
     a = _apply_axis(a, dft_matrix(ny, ky, -1.0), -3)
     a = _apply_axis(a, dft_matrix(nx, kx, -1.0), -4)
@@ -171,8 +179,10 @@ def inverse_spectrum(yhat: np.ndarray, spec: LayerSpec) -> np.ndarray:
     a = _apply_axis(a, dft_matrix(ny, ky, +1.0).T, -3)
     a = _apply_axis(a, dft_matrix(nz, kz, +1.0).T, -2)
     c = hermitian_weights(nt, kt)
-    a = _apply_last(a * c, dft_matrix(nt, kt, +1.0).T)
-    return a.real / float(spec.npoints)
+    e = dft_matrix(nt, kt, +1.0) * c[:, None]           # e[j, n] = c_kt exp(+2 pi i kt n / Nt)
+    # real part of sum_j a[..., j] e[j, n]
+    y = np.matmul(a.real, e.real) - np.matmul(a.imag, e.imag)
+    return y / float(spec.npoints)
 
 
 def spectral_conv_fwd(x: np.ndarray, r: np.ndarray, spec: LayerSpec, return_xhat: bool = False):
@@ -187,7 +197,8 @@ def spectral_conv_fwd(x: np.ndarray, r: np.ndarray, spec: LayerSpec, return_xhat
 # ----------------------------------------------------------------------------------------
 def channel_affine(x: np.ndarray, w: np.ndarray, b: np.ndarray | None) -> np.ndarray:
     """y[b,o,n] = sum_i W[o,i] x[b,i,n] + b[o]   (eq. (4), contraction along channels)."""
-    y = np.einsum("oi,bixyzt->boxyzt", np.asarray(w, np.float64), np.asarray(x, np.float64))
+    y = np.tensordot(np.asarray(w, np.float64), np.asarray(x, np.float64), axes=([1], [1]))   # (o, b, grid)
+    y = np.moveaxis(y, 0, 1)
     if b is not None:
         y = y + np.asarray(b, np.float64)[None, :, None, None, None, None]
     return y
@@ -372,6 +383,25 @@ def inverse_at_points(yhat, spec: LayerSpec, points: np.ndarray) -> np.ndarray:
         v = np.einsum("...xyzt,x,y,z,t->...", yhat, ex, ey, ez, et)
         out[..., p] = v.real / float(spec.npoints)
     return out
+
+
+def separable_weight_grads(gz_factors, x_factors):
+    """gW and gb of block_bwd() when both gz and x are rank-one fields (identity activation).
+
+    gW[o,i] = sum_{b,n} gz[b,o,n] x[b,i,n] and gb[o] = sum_{b,n} gz[b,o,n]; for products of
+    one-dimensional factors the sum over the grid is the product of the per-axis sums.
+    Factors: four arrays (B, C, N_a) each.
+    """
+    gw = None
+    gb = None
+    for ga, xa in zip(gz_factors, x_factors):
+        ga = np.asarray(ga, np.float64)
+        xa = np.asarray(xa, np.float64)
+        pair = np.einsum("bon,bin->boi", ga, xa)
+        single = ga.sum(axis=2)
+        gw = pair if gw is None else gw * pair
+        gb = single if gb is None else gb * single
+    return gw.sum(axis=0), gb.sum(axis=0)
 
 
 # ----------------------------------------------------------------------------------------

@@ -6,6 +6,7 @@
 #include <cstdarg>
 #include <cstdio>
 #include <cstring>
+#include <vector>
 
 namespace {
 
@@ -127,6 +128,39 @@ int check_ws(const Plan& p, void* ws, size_t ws_bytes) {
     }                                                                       \
   } while (0)
 
+// ---- optional per-stage timing (benchmarks only) ------------------------------------------
+struct TimingRecord { int stage; hipEvent_t start, stop; };
+constexpr int kMaxTimingRecords = 8192;
+bool g_timing_on = false;
+int g_timing_used = 0;
+std::vector<TimingRecord> g_timing;     // events are created once and reused
+
+bool timing_begin(int stage, hipStream_t s) {
+  if (!g_timing_on || g_timing_used >= kMaxTimingRecords) return false;
+  if (g_timing_used == (int)g_timing.size()) {
+    TimingRecord r{stage, nullptr, nullptr};
+    if (hipEventCreate(&r.start) != hipSuccess || hipEventCreate(&r.stop) != hipSuccess) return false;
+    g_timing.push_back(r);
+  }
+  g_timing[g_timing_used].stage = stage;
+  return hipEventRecord(g_timing[g_timing_used].start, s) == hipSuccess;
+}
+void timing_end(hipStream_t s) {
+  hipEventRecord(g_timing[g_timing_used].stop, s);
+  ++g_timing_used;
+}
+
+#define FNO_STAGE(stage, s, expr)                 \
+  do {                                            \
+    const bool timed_ = timing_begin((stage), (s)); \
+    hipError_t e_ = (expr);                       \
+    if (timed_) timing_end((s));                  \
+    if (e_ != hipSuccess) {                       \
+      set_detail("HIP error: %s", hipGetErrorString(e_)); \
+      return FNO_EHIP;                            \
+    }                                             \
+  } while (0)
+
 template <class T> T* at(void* ws, size_t off) { return reinterpret_cast<T*>(static_cast<char*>(ws) + off); }
 
 int build_tables(const Plan& p, void* ws, hipStream_t s) {
@@ -140,12 +174,12 @@ int forward_chain(const Plan& p, void* ws, const float* field, int C, float2* sp
   const int64_t bc = (int64_t)p.B * C;
   float2* a1 = at<float2>(ws, p.off_a1);
   float2* a2 = at<float2>(ws, p.off_a2);
-  FNO_HIP(fno::launch_tz_fwd(field, a1, at<float2>(ws, p.off_twt), at<float2>(ws, p.off_tw[2]),
+  FNO_STAGE(FNO_STAGE_TZ_FWD, s, fno::launch_tz_fwd(field, a1, at<float2>(ws, p.off_twt), at<float2>(ws, p.off_tw[2]),
                              bc * p.N[0] * p.N[1], p.ax[2], p.Nt, p.mt, s));
   const int64_t in_y = (int64_t)p.L[2] * p.mt;
-  FNO_HIP(fno::launch_axis_fwd(a1, a2, at<float2>(ws, p.off_tw[1]), bc * p.N[0], p.ax[1], in_y, s));
+  FNO_STAGE(FNO_STAGE_Y_FWD, s, fno::launch_axis_fwd(a1, a2, at<float2>(ws, p.off_tw[1]), bc * p.N[0], p.ax[1], in_y, s));
   const int64_t in_x = in_y * p.L[1];
-  FNO_HIP(fno::launch_axis_fwd(a2, spec, at<float2>(ws, p.off_tw[0]), bc, p.ax[0], in_x, s));
+  FNO_STAGE(FNO_STAGE_X_FWD, s, fno::launch_axis_fwd(a2, spec, at<float2>(ws, p.off_tw[0]), bc, p.ax[0], in_x, s));
   return FNO_OK;
 }
 
@@ -157,9 +191,9 @@ int inverse_chain(const Plan& p, void* ws, const float2* spec, int C, float* out
   float2* a2 = at<float2>(ws, p.off_a2);
   const int64_t in_y = (int64_t)p.L[2] * p.mt;
   const int64_t in_x = in_y * p.L[1];
-  FNO_HIP(fno::launch_axis_inv(spec, a2, at<float2>(ws, p.off_tw[0]), bc, p.ax[0], in_x, s));
-  FNO_HIP(fno::launch_axis_inv(a2, a1, at<float2>(ws, p.off_tw[1]), bc * p.N[0], p.ax[1], in_y, s));
-  FNO_HIP(fno::launch_zt_inv(a1, out, at<float2>(ws, p.off_twt), at<float2>(ws, p.off_tw[2]), p.B, C,
+  FNO_STAGE(FNO_STAGE_X_INV, s, fno::launch_axis_inv(spec, a2, at<float2>(ws, p.off_tw[0]), bc, p.ax[0], in_x, s));
+  FNO_STAGE(FNO_STAGE_Y_INV, s, fno::launch_axis_inv(a2, a1, at<float2>(ws, p.off_tw[1]), bc * p.N[0], p.ax[1], in_y, s));
+  FNO_STAGE(FNO_STAGE_ZT_INV, s, fno::launch_zt_inv(a1, out, at<float2>(ws, p.off_twt), at<float2>(ws, p.off_tw[2]), p.B, C,
                              p.N[0], p.N[1], p.ax[2], p.Nt, p.mt, ep, s));
   return FNO_OK;
 }
@@ -172,7 +206,7 @@ int conv_fwd_common(const Plan& p, const float* x, const float* R, float* out, f
   rc = forward_chain(p, ws, x, p.Ci, xh, s);
   if (rc != FNO_OK) return rc;
   float2* yh = at<float2>(ws, p.off_s2);
-  FNO_HIP(fno::launch_mix_fwd(xh, reinterpret_cast<const float2*>(R), yh, p.B, p.Ci, p.Co, p.K, p.mt,
+  FNO_STAGE(FNO_STAGE_MIX, s, fno::launch_mix_fwd(xh, reinterpret_cast<const float2*>(R), yh, p.B, p.Ci, p.Co, p.K, p.mt,
                               p.Nt, 1.0 / double(p.Npts), s));
   return inverse_chain(p, ws, yh, p.Co, out, ep, s);
 }
@@ -193,7 +227,7 @@ int conv_bwd_common(const Plan& p, const float* x, const float* xhat_saved, cons
   rc = forward_chain(p, ws, gz, p.Co, gh, s);
   if (rc != FNO_OK) return rc;
   float2* gxh = gx != nullptr ? at<float2>(ws, p.off_s2) : nullptr;
-  FNO_HIP(fno::launch_mix_bwd(xh, reinterpret_cast<const float2*>(R), gh,
+  FNO_STAGE(FNO_STAGE_MIX_BWD, s, fno::launch_mix_bwd(xh, reinterpret_cast<const float2*>(R), gh,
                               reinterpret_cast<float2*>(gR), gxh, p.B, p.Ci, p.Co, p.K, p.mt, p.Nt,
                               1.0 / double(p.Npts), s));
   if (gx != nullptr) return inverse_chain(p, ws, gxh, p.Ci, gx, ep, s);
@@ -290,7 +324,7 @@ int fno_block_bwd(const fno_desc* desc, const float* x, const float* R, const fl
   double* part = at<double>(ws, p.off_part);
   const int mse = (desc->flags & FNO_FLAG_MSE_TARGET) ? 1 : 0;
   const double mse_scale = 2.0 / (double(p.B) * double(p.Co) * double(p.Npts));
-  FNO_HIP(fno::launch_bwd_pointwise(z_saved, gout, x, gz, part, p.part_blocks, p.B, p.Ci, p.Co,
+  FNO_STAGE(FNO_STAGE_BWD_POINTWISE, s, fno::launch_bwd_pointwise(z_saved, gout, x, gz, part, p.part_blocks, p.B, p.Ci, p.Co,
                                     p.Npts, desc->activation, mse, mse_scale, s));
   if (gW != nullptr || gb != nullptr)
     FNO_HIP(fno::launch_reduce_partials(part, p.part_blocks, p.Co, p.Ci, gW, gb, s));
@@ -318,6 +352,31 @@ int fno_pointwise_mlp2(int32_t batch, int32_t c_in, int32_t hidden, int32_t c_ou
   if (c_in > 32 || c_out > 4 || batch > 65535) { set_detail("pointwise_mlp2 covers c_in <= 32, c_out <= 4, batch <= 65535"); return FNO_EUNSUPPORTED; }
   FNO_HIP(fno::launch_pointwise_mlp2(batch, c_in, hidden, c_out, npoints, x, W1, b1, W2, b2, y,
                                      static_cast<hipStream_t>(stream)));
+  return FNO_OK;
+}
+
+int fno_timing_enable(int on) {
+  g_timing_on = on != 0;
+  g_timing_used = 0;
+  return FNO_OK;
+}
+
+int fno_timing_read(int32_t* stages, float* ms, int32_t capacity, int32_t* count) {
+  if (count == nullptr || capacity < 0 || (capacity > 0 && (stages == nullptr || ms == nullptr))) {
+    set_detail("timing_read needs count, and stages/ms when capacity > 0");
+    return FNO_EINVAL;
+  }
+  int n = 0;
+  for (int r = 0; r < g_timing_used && n < capacity; ++r) {
+    FNO_HIP(hipEventSynchronize(g_timing[r].stop));
+    float t = 0.f;
+    FNO_HIP(hipEventElapsedTime(&t, g_timing[r].start, g_timing[r].stop));
+    stages[n] = g_timing[r].stage;
+    ms[n] = t;
+    ++n;
+  }
+  *count = n;
+  g_timing_used = 0;
   return FNO_OK;
 }
 

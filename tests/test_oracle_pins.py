@@ -410,3 +410,21 @@ def test_network_pieces():
     hvec = w1 @ v[0, :, 3, 1, 0, 2] + b1
     from scipy.stats import norm
     assert abs(u[0, 0, 3, 1, 0, 2] - (w2 @ (hvec * norm.cdf(hvec)) + b2)[0]) < 1e-13
+
+
+def test_separable_weight_grads_match_block_bwd():
+    spec = O.LayerSpec((4, 5, 6, 4), (1, 2, 2, 2), 0)
+    rng = _rng(30)
+    fx = [rng.integers(-15, 16, size=(2, 3, n)) / 8.0 for n in spec.grid]
+    fg = [rng.integers(-15, 16, size=(2, 3, n)) / 8.0 for n in spec.grid]
+
+    def outer(f):
+        return (f[0][:, :, :, None, None, None] * f[1][:, :, None, :, None, None]
+                * f[2][:, :, None, None, :, None] * f[3][:, :, None, None, None, :])
+
+    x, g = outer(fx), outer(fg)
+    _, r = _rand_layer(31, spec, b=2, cin=3, cout=3)
+    w = rng.standard_normal((3, 3))
+    ref = O.block_bwd(x, r, w, np.zeros(3), g, spec, "identity")
+    gw, gb = O.separable_weight_grads(fg, fx)
+    assert _rel(gw, ref["gW"]) < 1e-13 and _rel(gb, ref["gb"]) < 1e-13
