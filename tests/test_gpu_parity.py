@@ -142,8 +142,9 @@ def test_block_fwd_and_bwd_match_oracle(case, activation):
         assert rel(host(gx), ref["gx"]) <= TOL
         assert rel(host(gR), ref["gR"]) <= TOL
         assert rel(host(gW), ref["gW"]) <= TOL
-        # gb is a sum of terms of both signs: bound the error by the size of the summands
-        gb_scale = np.sqrt(np.sum(ref["gz"] ** 2, axis=(0, 2, 3, 4, 5)))
+        # gb is a sum of terms of either sign: where they cancel, the error is bounded by the
+        # size of the summands (root-sum-square), elsewhere by the sum itself
+        gb_scale = np.abs(ref["gb"]) + np.sqrt(np.sum(ref["gz"] ** 2, axis=(0, 2, 3, 4, 5)))
         assert np.max(np.abs(host(gb) - ref["gb"]) / np.maximum(gb_scale, 1e-300)) <= TOL
         # identical bits on a second run (fixed reduction order)
         gW2 = torch.empty_like(gW)
@@ -173,7 +174,7 @@ def test_one_hot_frequency_is_exactly_truncated():
     L = Layer(1, 1, 1, grid, modes)
     L.R[:] = 1.0
     n = np.meshgrid(*[np.arange(g) for g in grid], indexing="ij")
-    for k4, kept in [((3, -4, 2, 2), True), ((4, 0, 0, 0), False), ((0, 0, 5, 1), False), ((1, 1, 1, 3), False),
+    for k4, kept in [((3, -4, 2, 2), True), ((5, 0, 0, 0), False), ((4, 0, 0, 1), False), ((-4, 0, 0, 1), True), ((0, 0, 5, 1), False), ((1, 1, 1, 3), False),
                      ((-4, -4, -4, 0), True)]:
         th = 2 * np.pi * sum(k4[a] * n[a] / grid[a] for a in range(4))
         x = np.cos(th)[None, None].astype(np.float32)
@@ -182,7 +183,7 @@ def test_one_hot_frequency_is_exactly_truncated():
         if kept:
             assert rel(y, yo) <= TOL and np.max(np.abs(yo)) > 0.1
         else:
-            assert np.max(np.abs(yo)) < 1e-12 and np.max(np.abs(y)) < 2e-6
+            assert np.max(np.abs(yo)) < 1e-7 and np.max(np.abs(y)) < 2e-6   # float32 rounding of the input leaks a little
 
 
 def test_cfg2_block_forward_full_size_elementwise():
