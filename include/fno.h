@@ -19,7 +19,8 @@
  *     read during the call only.
  *   - Work is enqueued on `stream` (a hipStream_t passed as void*, NULL = default stream) and
  *     the call returns without waiting.
- *   - Complex tensors are interleaved (re, im) float pairs.
+ *   - Complex tensors are interleaved (re, im) float pairs.  Grid-sized and mode-sized tensors
+ *     must be 16-byte aligned (FNO_EINVAL otherwise).
  *   - Return value: FNO_OK (0) or a negative FNO_E* code.  On an argument error nothing is
  *     launched and no output byte is written.
  *   - Two calls that share a workspace or an output must be ordered by the caller.

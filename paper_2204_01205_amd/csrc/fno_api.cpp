@@ -80,14 +80,18 @@ int make_plan(const fno_desc* d, bool need_block, bool need_bwd_block, Plan* p) 
   {
     AxisPlan az{p->N[2], p->L[2], p->npos[2], 1, p->N[2]};
     bool ok = false;
-    for (int m = largest_pow2_divisor(p->N[2], fno::kMaxFftM); m >= 1; m >>= 1) {
+    // 16 suits the tile of the matrix-core inverse kernel best; then larger, then smaller splits
+    const int order[6] = {16, 32, 8, 4, 2, 1};
+    for (int c = 0; c < 6 && !ok; ++c) {
+      const int m = order[c];
+      if (m > fno::kMaxFftM || p->N[2] % m) continue;
       az.M = m; az.P = p->N[2] / m;
-      if (fno::tz_fwd_fits(az, p->Nt, p->mt) && fno::zt_inv_fits(az, p->Nt, p->mt, Cm)) { ok = true; break; }
+      ok = fno::tz_fwd_fits(az, p->Nt, p->mt) &&
+           (fno::zt_mfma_fits(az, p->Nt, p->mt, Cm, Cm) || fno::zt_inv_fits(az, p->Nt, p->mt, Cm));
     }
     if (!ok) { set_detail("an Nz x Nt plane with this many channels does not fit the LDS tiles"); return FNO_EUNSUPPORTED; }
     p->ax[2] = az;
   }
-  if (need_bwd_block && (p->Co * p->Ci + p->Co > 512)) { set_detail("weight-gradient reduction covers Cout*(Cin+1) <= 512"); return FNO_EUNSUPPORTED; }
 
   // workspace
   size_t off = 0;
@@ -110,6 +114,15 @@ int make_plan(const fno_desc* d, bool need_block, bool need_bwd_block, Plan* p) 
   }
   p->total = off;
   return FNO_OK;
+}
+
+bool misaligned16(const void* a, const void* b = nullptr, const void* c = nullptr, const void* d = nullptr,
+                  const void* e = nullptr, const void* f = nullptr) {
+  const uintptr_t bits = reinterpret_cast<uintptr_t>(a) | reinterpret_cast<uintptr_t>(b) |
+                         reinterpret_cast<uintptr_t>(c) | reinterpret_cast<uintptr_t>(d) |
+                         reinterpret_cast<uintptr_t>(e) | reinterpret_cast<uintptr_t>(f);
+  if (bits & 15) { set_detail("tensor pointers must be 16-byte aligned"); return true; }
+  return false;
 }
 
 int check_ws(const Plan& p, void* ws, size_t ws_bytes) {
@@ -268,6 +281,7 @@ int fno_spectral_conv_fwd(const fno_desc* desc, const float* x, const float* R, 
   int rc = make_plan(desc, false, false, &p);
   if (rc != FNO_OK) return rc;
   if (x == nullptr || R == nullptr || y == nullptr) { set_detail("x, R and y are required"); return FNO_EINVAL; }
+  if (misaligned16(x, R, y, xhat_save)) return FNO_EINVAL;
   rc = check_ws(p, ws, ws_bytes);
   if (rc != FNO_OK) return rc;
   fno::Epilogue ep{nullptr, 0, nullptr, 0, 0, nullptr, nullptr, 0};
@@ -282,6 +296,7 @@ int fno_spectral_conv_bwd(const fno_desc* desc, const float* x, const float* xha
   if (rc != FNO_OK) return rc;
   if (R == nullptr || gy == nullptr) { set_detail("R and gy are required"); return FNO_EINVAL; }
   if (gR != nullptr && x == nullptr && xhat_saved == nullptr) { set_detail("gR needs x or xhat_saved"); return FNO_EINVAL; }
+  if (misaligned16(x, xhat_saved, R, gy, gx, gR)) return FNO_EINVAL;
   rc = check_ws(p, ws, ws_bytes);
   if (rc != FNO_OK) return rc;
   if (gx == nullptr && gR == nullptr) return FNO_OK;
@@ -299,6 +314,7 @@ int fno_block_fwd(const fno_desc* desc, const float* x, const float* R, const fl
   int rc = make_plan(desc, true, false, &p);
   if (rc != FNO_OK) return rc;
   if (x == nullptr || R == nullptr || W == nullptr || out == nullptr) { set_detail("x, R, W and out are required"); return FNO_EINVAL; }
+  if (misaligned16(x, R, out, z_save, xhat_save)) return FNO_EINVAL;
   rc = check_ws(p, ws, ws_bytes);
   if (rc != FNO_OK) return rc;
   fno::Epilogue ep{x, p.Ci, W, p.Ci, 1, b, z_save, desc->activation};
@@ -315,6 +331,7 @@ int fno_block_bwd(const fno_desc* desc, const float* x, const float* R, const fl
     set_detail("x, R, W, z_saved and gout are required");
     return FNO_EINVAL;
   }
+  if (misaligned16(x, R, z_saved, xhat_saved, gout, gx) || misaligned16(gR)) return FNO_EINVAL;
   rc = check_ws(p, ws, ws_bytes);
   if (rc != FNO_OK) return rc;
   hipStream_t s = static_cast<hipStream_t>(stream);

@@ -76,5 +76,6 @@ constexpr int kLdsBudget = 60 * 1024;
 bool tz_fwd_fits(AxisPlan az, int Nt, int mt);
 bool zt_inv_fits(AxisPlan az, int Nt, int mt, int Co);
 bool axis_fits(AxisPlan ax);
+bool zt_mfma_fits(AxisPlan az, int Nt, int mt, int Co, int Cu);
 
 }  // namespace fno

@@ -398,9 +398,160 @@ __global__ __launch_bounds__(kThreads) void zt_inv_kernel(
 }
 
 // ------------------------------------------------------------------------------------------
+// The same stage for t-lengths that are multiples of 16, with the two dense contractions on
+// the matrix cores.  Per grid point the pre-activation is one inner product of length Cu + 2 mt:
+//     z[o] = b[o] + sum_i W[o][i] u[i]  +  sum_kt ( Re V[o][kt] cos(th) - Im V[o][kt] sin(th) )
+// i.e. the channel-linear term of eq. (2) and the complex-to-real step over t share the
+// accumulator.  v_mfma_f32_4x4x1 (16 independent 4x4 outer products per wave, full fp32) fits
+// it without padding: a lane owns 4 consecutive t of one z-row (one float4 of u and of out);
+// the 4 lanes of an MFMA block lie in the same row, so they share the A column
+// (W[4T..4T+3][i] or V[4T..4T+3][row][kt]) while each lane brings its own B value (u or the
+// twiddle at its t).  Result register r of tile T is channel 4T+r at the lane's own point.
+// Blocks that share a (b,nx,ny) column are placed on one XCD so the column's spectrum tile
+// is fetched into that XCD's L2 once.
+// ------------------------------------------------------------------------------------------
+typedef float v4f __attribute__((ext_vector_type(4)));
+
+template <int NT, int MZ, int CT>
+__global__ __launch_bounds__(256) void zt_inv_mfma_kernel(
+    const float2* __restrict__ a, float* __restrict__ out, const float2* __restrict__ twt,
+    const float2* __restrict__ twz, int Co, int NxNy, long long ncols, int Nz, int Lz, int nposz,
+    int mt, int Q, EpiArgs ep) {
+  HIP_DYNAMIC_SHARED(float, smem)
+  constexpr int CP = 4 * CT;                 // channels padded to whole MFMA tiles
+  constexpr int CI = CP;                     // register file for the u loads
+  constexpr int QPR = NT / 4;                // float4 quads per row
+  const int Pz = Nz / MZ;
+  const int G = Pz / Q;
+  const int Rz = Q * MZ;
+  const int nthr = blockDim.x;               // == Rz * QPR
+  float2* V = reinterpret_cast<float2*>(smem);          // [CP][Rz][mt]
+  float* CS = smem + 2 * CP * Rz * mt;                  // [2 mt][NT]: cos rows and -sin rows
+  float* Wt = CS + 2 * mt * NT;                         // [Cu][CP]
+  const int tid = threadIdx.x;
+  const long long slot = blockIdx.x >> 3;
+  const int xcd = blockIdx.x & 7;
+  const long long col = (slot / G) * 8 + xcd;
+  const int g = (int)(slot % G);
+  if (col >= ncols) return;
+  const long long b = col / NxNy;
+  const long long xy = col % NxNy;
+  const int quad = tid % QPR;
+  const int row = tid / QPR;
+  const int z = Pz * (row / Q) + g * Q + (row % Q);
+  const long long Npts = (long long)NxNy * Nz * NT;
+  const long long off = (xy * Nz + z) * NT + 4 * quad;
+  const int kmin = nposz - Lz, kmax = nposz - 1;
+  const bool lin = ep.u != nullptr;
+
+  // u loads go out first so they are in flight during the z stage
+  float4 xv[CI];
+  if (lin) {
+#pragma unroll
+    for (int i = 0; i < CI; ++i)
+      if (i < ep.Cu) xv[i] = *reinterpret_cast<const float4*>(ep.u + (b * ep.Cu + i) * Npts + off);
+  }
+  for (int idx = tid; idx < 2 * mt * NT; idx += nthr) {
+    const int k = idx / NT, t = idx - k * NT;
+    const float2 w = twt[(k >> 1) * NT + t];
+    CS[idx] = (k & 1) ? w.y : w.x;
+  }
+  if (lin) {
+    for (int idx = tid; idx < ep.Cu * CP; idx += nthr) {
+      const int i = idx / CP, o = idx - i * CP;
+      Wt[idx] = o < Co ? ep.W[o * ep.w_so + i * ep.w_si] : 0.f;
+    }
+  }
+
+  // z stage: twiddled gather into MZ bins, inverse FFT over n1 (as in the generic kernel)
+  for (int idx = tid; idx < Co * mt * Q; idx += nthr) {
+    const int q = idx % Q;
+    const int kt = (idx / Q) % mt;
+    const int o = idx / (Q * mt);
+    const int n2 = g * Q + q;
+    const float2* src = a + (((b * Co + o) * NxNy + xy) * Lz) * mt + kt;
+    float2 gbin[MZ];
+#pragma unroll
+    for (int m = 0; m < MZ; ++m) {
+      float2 acc = make_float2(0.f, 0.f);
+      for (int k = kmin + posmod(m - kmin, MZ); k <= kmax; k += MZ) {
+        const int j = k >= 0 ? k : k + Lz;
+        acc = cfmac(src[j * mt], twz[j * Pz + n2], acc);
+      }
+      gbin[m] = acc;
+    }
+    fft_reg<MZ, +1>(gbin);
+#pragma unroll
+    for (int n1 = 0; n1 < MZ; ++n1) V[((o * Rz) + n1 * Q + q) * mt + kt] = gbin[bitrev<MZ>(n1)];
+  }
+  // channels of the padding tiles: finite values so the unused MFMA rows stay harmless
+  for (int idx = tid; idx < (CP - Co) * Rz * mt; idx += nthr) V[Co * Rz * mt + idx] = make_float2(0.f, 0.f);
+  __syncthreads();
+
+  v4f acc[CT][4];
+#pragma unroll
+  for (int T = 0; T < CT; ++T) {
+    v4f init;
+#pragma unroll
+    for (int r = 0; r < 4; ++r) init[r] = (ep.bias != nullptr && 4 * T + r < Co) ? ep.bias[4 * T + r] : 0.f;
+#pragma unroll
+    for (int s = 0; s < 4; ++s) acc[T][s] = init;
+  }
+  const int lane4 = tid & 3;
+  if (lin) {
+#pragma unroll
+    for (int i = 0; i < CI; ++i) {
+      if (i < ep.Cu) {
+#pragma unroll
+        for (int T = 0; T < CT; ++T) {
+          const float w = Wt[i * CP + 4 * T + lane4];
+          acc[T][0] = __builtin_amdgcn_mfma_f32_4x4x1f32(w, xv[i].x, acc[T][0], 0, 0, 0);
+          acc[T][1] = __builtin_amdgcn_mfma_f32_4x4x1f32(w, xv[i].y, acc[T][1], 0, 0, 0);
+          acc[T][2] = __builtin_amdgcn_mfma_f32_4x4x1f32(w, xv[i].z, acc[T][2], 0, 0, 0);
+          acc[T][3] = __builtin_amdgcn_mfma_f32_4x4x1f32(w, xv[i].w, acc[T][3], 0, 0, 0);
+        }
+      }
+    }
+  }
+  const float2* vlane = V + (lane4 * Rz + row) * mt;
+  for (int kt = 0; kt < mt; ++kt) {
+    const float4 c4 = *reinterpret_cast<const float4*>(CS + (2 * kt) * NT + 4 * quad);
+    const float4 s4 = *reinterpret_cast<const float4*>(CS + (2 * kt + 1) * NT + 4 * quad);
+#pragma unroll
+    for (int T = 0; T < CT; ++T) {
+      const float2 v = vlane[(4 * T * Rz) * mt + kt];
+      acc[T][0] = __builtin_amdgcn_mfma_f32_4x4x1f32(v.x, c4.x, acc[T][0], 0, 0, 0);
+      acc[T][1] = __builtin_amdgcn_mfma_f32_4x4x1f32(v.x, c4.y, acc[T][1], 0, 0, 0);
+      acc[T][2] = __builtin_amdgcn_mfma_f32_4x4x1f32(v.x, c4.z, acc[T][2], 0, 0, 0);
+      acc[T][3] = __builtin_amdgcn_mfma_f32_4x4x1f32(v.x, c4.w, acc[T][3], 0, 0, 0);
+      acc[T][0] = __builtin_amdgcn_mfma_f32_4x4x1f32(v.y, s4.x, acc[T][0], 0, 0, 0);
+      acc[T][1] = __builtin_amdgcn_mfma_f32_4x4x1f32(v.y, s4.y, acc[T][1], 0, 0, 0);
+      acc[T][2] = __builtin_amdgcn_mfma_f32_4x4x1f32(v.y, s4.z, acc[T][2], 0, 0, 0);
+      acc[T][3] = __builtin_amdgcn_mfma_f32_4x4x1f32(v.y, s4.w, acc[T][3], 0, 0, 0);
+    }
+  }
+
+#pragma unroll
+  for (int T = 0; T < CT; ++T) {
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+      const int o = 4 * T + r;
+      if (o < Co) {
+        float4 zv = make_float4(acc[T][0][r], acc[T][1][r], acc[T][2][r], acc[T][3][r]);
+        const long long oidx = (b * Co + o) * Npts + off;
+        if (ep.zsave != nullptr) *reinterpret_cast<float4*>(ep.zsave + oidx) = zv;
+        if (ep.act) zv = make_float4(gelu_f(zv.x), gelu_f(zv.y), gelu_f(zv.z), gelu_f(zv.w));
+        *reinterpret_cast<float4*>(out + oidx) = zv;
+      }
+    }
+  }
+}
+
+// ------------------------------------------------------------------------------------------
 // Backward pointwise: gz = g * act'(z); partial sums for gb and gW
 // ------------------------------------------------------------------------------------------
 constexpr int kBwdTile = 256;      // points per tile (= threads)
+constexpr int kBwdPairs = 5;       // sums per thread: covers Cout*(Cin+1) up to 1280
 
 __global__ __launch_bounds__(kThreads) void bwd_pointwise_kernel(
     const float* __restrict__ z, const float* __restrict__ gout, const float* __restrict__ x,
@@ -414,8 +565,10 @@ __global__ __launch_bounds__(kThreads) void bwd_pointwise_kernel(
   const long long tiles_per_b = (N + kBwdTile - 1) / kBwdTile;
   const long long ntiles = tiles_per_b * B;
   const int npairs = Co * Ci + Co;
-  // each thread owns up to 2 of the Co*Ci + Co sums (npairs <= 2 * kThreads is checked on the host)
-  double acc0 = 0.0, acc1 = 0.0;
+  // each thread owns up to kBwdPairs of the Co*Ci + Co sums (checked on the host)
+  double acc[kBwdPairs];
+#pragma unroll
+  for (int h = 0; h < kBwdPairs; ++h) acc[h] = 0.0;
   for (long long tile = blockIdx.x; tile < ntiles; tile += gridDim.x) {
     const long long b = tile / tiles_per_b;
     const long long p = (tile % tiles_per_b) * kBwdTile + tid;
@@ -435,7 +588,7 @@ __global__ __launch_bounds__(kThreads) void bwd_pointwise_kernel(
     for (int i = 0; i < Ci; ++i) Xs[i * sR + tid] = live ? x[(b * Ci + i) * N + p] : 0.f;
     __syncthreads();
 #pragma unroll
-    for (int h = 0; h < 2; ++h) {
+    for (int h = 0; h < kBwdPairs; ++h) {
       const int q = tid + h * kThreads;
       if (q < npairs) {
         float s = 0.f;
@@ -447,13 +600,14 @@ __global__ __launch_bounds__(kThreads) void bwd_pointwise_kernel(
           const float* gr = Gs + (q - Co * Ci) * sR;
           for (int t = 0; t < kBwdTile; ++t) s += gr[t];
         }
-        if (h == 0) acc0 += double(s); else acc1 += double(s);
+        acc[h] += double(s);
       }
     }
     __syncthreads();
   }
-  if (tid < npairs) part[(long long)blockIdx.x * npairs + tid] = acc0;
-  if (tid + kThreads < npairs) part[(long long)blockIdx.x * npairs + tid + kThreads] = acc1;
+#pragma unroll
+  for (int h = 0; h < kBwdPairs; ++h)
+    if (tid + h * kThreads < npairs) part[(long long)blockIdx.x * npairs + tid + h * kThreads] = acc[h];
 }
 
 __global__ void reduce_partials_kernel(const double* __restrict__ part, int nblk, int Co, int Ci,
@@ -563,6 +717,13 @@ bool zt_inv_fits(AxisPlan az, int Nt, int mt, int Co) {
   return Co <= kMaxCo && zt_inv_lds(az, Nt, mt, Co) <= (size_t)(64 * 1024);
 }
 bool axis_fits(AxisPlan ax) { return (size_t)ax.N * 8 <= (size_t)kLdsBudget; }
+int mfma_q(AxisPlan az, int Nt);
+size_t zt_mfma_lds(AxisPlan az, int Nt, int mt, int Co, int Cu, int q);
+bool zt_mfma_fits(AxisPlan az, int Nt, int mt, int Co, int Cu) {
+  const int q = mfma_q(az, Nt);
+  const int CT = (Co + 3) / 4 <= 2 ? 2 : ((Co + 3) / 4 <= 5 ? 5 : 8);
+  return q > 0 && Co <= kMaxCo && Cu <= 4 * CT && zt_mfma_lds(az, Nt, mt, Co, Cu, q) <= (size_t)(64 * 1024);
+}
 
 hipError_t launch_axis_table(float2* tw, AxisPlan ax, hipStream_t s) {
   const int n = ax.L * ax.P;
@@ -640,17 +801,73 @@ hipError_t launch_mix_bwd(const float2* xh, const float2* R, const float2* gh, f
   return hipGetLastError();
 }
 
+// Tile of the matrix-core kernel: Q residue classes whose Rz = Q*M rows times Nt points make
+// 256..1024 points (64..256 threads) and whose Q adjacent rows span at least 128 bytes.
+int mfma_q(AxisPlan az, int Nt) {
+  if (Nt != 16 && Nt != 32) return 0;
+  if (az.M != 8 && az.M != 16 && az.M != 32) return 0;
+  int best = 0, best_score = -1;
+  for (int q = 1; q <= az.P; ++q) {
+    if (az.P % q) continue;
+    const int thr = q * az.M * Nt / 4;
+    if (thr > 256) break;
+    if (thr % 64) continue;
+    const int score = (q * Nt >= 32 ? 2 : 0) + (thr >= 128 ? 1 : 0);
+    if (score > best_score) { best_score = score; best = q; }
+  }
+  return best;
+}
+
+size_t zt_mfma_lds(AxisPlan az, int Nt, int mt, int Co, int Cu, int q) {
+  const int CP = 4 * ((Co + 3) / 4 <= 2 ? 2 : ((Co + 3) / 4 <= 5 ? 5 : 8));
+  return ((size_t)2 * CP * q * az.M * mt + (size_t)2 * mt * Nt + (size_t)Cu * CP) * 4;
+}
+
 hipError_t launch_zt_inv(const float2* a, float* out, const float2* twt, const float2* twz, int B,
                          int Co, int Nx, int Ny, AxisPlan az, int Nt, int mt, Epilogue ep,
                          hipStream_t s) {
-  const int Q = pick_q(az, Nt);
-  const int G = az.P / Q;
-  const int64_t nblk = (int64_t)B * Nx * Ny * G;
-  if (nblk <= 0) return hipSuccess;
-  if (nblk > 0x7fffffffLL || Co > kMaxCo) return hipErrorInvalidValue;
-  const size_t lds = zt_inv_lds(az, Nt, mt, Co);
+  const int64_t ncols = (int64_t)B * Nx * Ny;
+  if (ncols <= 0) return hipSuccess;
+  if (Co > kMaxCo) return hipErrorInvalidValue;
   EpiArgs e{ep.u, ep.Cu, ep.W, ep.w_so, ep.w_si, ep.bias, ep.zsave, ep.act};
   const int NxNy = Nx * Ny;
+  const int CT = (Co + 3) / 4 <= 2 ? 2 : ((Co + 3) / 4 <= 5 ? 5 : 8);
+  const int qf = mfma_q(az, Nt);
+  const bool aligned = ((reinterpret_cast<uintptr_t>(out) | reinterpret_cast<uintptr_t>(ep.u) |
+                         reinterpret_cast<uintptr_t>(ep.zsave)) & 15) == 0;
+  if (qf > 0 && aligned && (ep.u == nullptr || ep.Cu <= 4 * CT) &&
+      zt_mfma_lds(az, Nt, mt, Co, ep.u ? ep.Cu : 0, qf) <= (size_t)(64 * 1024)) {
+    const int G = az.P / qf;
+    const int64_t nblk = ((ncols + 7) / 8) * 8 * G;
+    if (nblk > 0x7fffffffLL) return hipErrorInvalidValue;
+    const int thr = qf * az.M * Nt / 4;
+    const size_t lds = zt_mfma_lds(az, Nt, mt, Co, ep.u ? ep.Cu : 0, qf);
+#define FNO_ZTM(NTV, MZV, CTV)                                                                     \
+  hipLaunchKernelGGL((zt_inv_mfma_kernel<NTV, MZV, CTV>), dim3((unsigned)nblk), dim3(thr), lds, s, \
+                     a, out, twt, twz, Co, NxNy, (long long)ncols, az.N, az.L, az.npos, mt, qf, e)
+#define FNO_ZTM_CT(NTV, MZV)                            \
+  do {                                                  \
+    if (CT == 2) FNO_ZTM(NTV, MZV, 2);                  \
+    else if (CT == 5) FNO_ZTM(NTV, MZV, 5);             \
+    else FNO_ZTM(NTV, MZV, 8);                          \
+  } while (0)
+#define FNO_ZTM_M(NTV)                                  \
+  do {                                                  \
+    if (az.M == 8) FNO_ZTM_CT(NTV, 8);                  \
+    else if (az.M == 16) FNO_ZTM_CT(NTV, 16);           \
+    else FNO_ZTM_CT(NTV, 32);                           \
+  } while (0)
+    if (Nt == 16) FNO_ZTM_M(16); else FNO_ZTM_M(32);
+#undef FNO_ZTM_M
+#undef FNO_ZTM_CT
+#undef FNO_ZTM
+    return hipGetLastError();
+  }
+  const int Q = pick_q(az, Nt);
+  const int G = az.P / Q;
+  const int64_t nblk = ncols * G;
+  if (nblk > 0x7fffffffLL) return hipErrorInvalidValue;
+  const size_t lds = zt_inv_lds(az, Nt, mt, Co);
 #define FNO_ZT_CALL(COV)                                                                          \
   FNO_DISPATCH_M(az.M, hipLaunchKernelGGL((zt_inv_kernel<MM, COV>), dim3((unsigned)nblk),         \
                                           dim3(kThreads), lds, s, a, out, twt, twz, Co, NxNy,     \
@@ -670,7 +887,7 @@ int bwd_pointwise_blocks(int B, int64_t N) {
 hipError_t launch_bwd_pointwise(const float* z, const float* gout, const float* x, float* gz_out,
                                 double* part, int nblk, int B, int Ci, int Co, int64_t N, int act,
                                 int mse_target, double mse_scale, hipStream_t s) {
-  if (Co * Ci + Co > 2 * kThreads) return hipErrorInvalidValue;
+  if (Co * Ci + Co > kBwdPairs * kThreads) return hipErrorInvalidValue;
   const size_t lds = (size_t)(Co + Ci) * (kBwdTile + 1) * 4;
   hipLaunchKernelGGL(bwd_pointwise_kernel, dim3((unsigned)nblk), dim3(kThreads), lds, s, z, gout,
                      x, gz_out, part, B, Ci, Co, (long long)N, act, mse_target, (float)mse_scale);
