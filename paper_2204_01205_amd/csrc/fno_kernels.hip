@@ -140,6 +140,102 @@ __global__ __launch_bounds__(kThreads) void tz_fwd_kernel(
 }
 
 // ------------------------------------------------------------------------------------------
+// Forward (t, z) for power-of-two Nt (16, 32, 64): float4 loads issued up front, the t stage as
+// a real-input FFT of one z-row per thread (an NT/2-point complex FFT of the even/odd samples
+// plus the split step), z twiddles in LDS.
+// ------------------------------------------------------------------------------------------
+// X[K] = E[K] + w^K O[K],  E = (Z[K] + conj Z[H-K]) / 2,  O = (Z[K] - conj Z[H-K]) / (2i)
+template <int NT, int K>
+__device__ __forceinline__ void rfft_bin(const float2 (&zc)[NT / 2], int mt, float2* __restrict__ tcol, int tstride) {
+  constexpr int H = NT / 2;
+  if (K < mt) {
+    const float2 zk = zc[bitrev<H>(K % H)];
+    const float2 zm = zc[bitrev<H>((H - K) % H)];
+    const float2 e = make_float2(0.5f * (zk.x + zm.x), 0.5f * (zk.y - zm.y));
+    const float2 od = make_float2(0.5f * (zk.y + zm.y), -0.5f * (zk.x - zm.x));
+    tcol[K * tstride] = cadd(e, mul_root<NT, K, -1>(od));
+  }
+}
+
+template <int NT, int... Ks>
+__device__ __forceinline__ void rfft_bins(const float2 (&zc)[NT / 2], int mt, float2* __restrict__ tcol, int tstride,
+                                          std::integer_sequence<int, Ks...>) {
+  (rfft_bin<NT, Ks>(zc, mt, tcol, tstride), ...);
+}
+
+template <int NT>
+__device__ __forceinline__ void rfft_row_bins(const float* __restrict__ srow, int mt, float2* __restrict__ tcol,
+                                              int tstride) {
+  constexpr int H = NT / 2;
+  float2 zc[H];
+#pragma unroll
+  for (int m4 = 0; m4 < NT / 4; ++m4) {
+    const float4 v = *reinterpret_cast<const float4*>(srow + 4 * m4);
+    zc[2 * m4] = make_float2(v.x, v.y);
+    zc[2 * m4 + 1] = make_float2(v.z, v.w);
+  }
+  fft_reg<H, -1>(zc);
+  rfft_bins<NT>(zc, mt, tcol, tstride, std::make_integer_sequence<int, H + 1>{});
+}
+
+template <int NT, int MZ>
+__global__ __launch_bounds__(kThreads) void tz_fwd_fast_kernel(
+    const float* __restrict__ x, float2* __restrict__ out, const float2* __restrict__ twz,
+    long long planes, int Nz, int Lz, int nposz, int mt, int ppb) {
+  HIP_DYNAMIC_SHARED(float, smem)
+  const int Pz = Nz / MZ;
+  constexpr int sS = NT + 4;                   // row stride of S in floats (keeps float4 alignment)
+  const int sT = Nz + 1;                       // row stride of T in float2
+  float* S = smem;                             // [ppb][Nz][sS]
+  float2* T = reinterpret_cast<float2*>(smem + ppb * Nz * sS);   // [ppb][mt][sT]
+  float2* TW = T + ppb * mt * sT;              // [Lz][Pz]
+  const int tid = threadIdx.x;
+  const long long plane0 = (long long)blockIdx.x * ppb;
+  const int np = (int)min((long long)ppb, planes - plane0);
+  const int plane_quads = Nz * (NT / 4);
+
+  const float4* src = reinterpret_cast<const float4*>(x + plane0 * Nz * NT);
+  for (int idx = tid; idx < np * plane_quads; idx += kThreads) {
+    const int row = idx / (NT / 4), q4 = idx - row * (NT / 4);
+    *reinterpret_cast<float4*>(S + row * sS + 4 * q4) = src[idx];
+  }
+  for (int idx = tid; idx < Lz * Pz; idx += kThreads) TW[idx] = twz[idx];
+  __syncthreads();
+
+  for (int row = tid; row < np * Nz; row += kThreads) {
+    const int p = row / Nz, z = row - p * Nz;
+    rfft_row_bins<NT>(S + row * sS, mt, T + (p * mt) * sT + z, sT);
+  }
+  __syncthreads();
+
+  if constexpr (MZ > 1) {
+    for (int idx = tid; idx < np * mt * Pz; idx += kThreads) {
+      const int n2 = idx % Pz, col = idx / Pz;
+      float2* base = T + col * sT + n2;
+      float2 a[MZ];
+#pragma unroll
+      for (int n1 = 0; n1 < MZ; ++n1) a[n1] = base[Pz * n1];
+      fft_reg<MZ, -1>(a);
+#pragma unroll
+      for (int m = 0; m < MZ; ++m) base[Pz * m] = a[bitrev<MZ>(m)];
+    }
+    __syncthreads();
+  }
+
+  for (int idx = tid; idx < np * Lz * mt; idx += kThreads) {
+    const int kt = idx % mt;
+    const int jz = (idx / mt) % Lz;
+    const int p = idx / (mt * Lz);
+    const int mj = posmod(kfreq(jz, Lz, nposz), MZ);
+    const float2* base = T + (p * mt + kt) * sT + Pz * mj;
+    const float2* w = TW + jz * Pz;
+    float2 acc = make_float2(0.f, 0.f);
+    for (int n2 = 0; n2 < Pz; ++n2) acc = cfma(w[n2], base[n2], acc);
+    out[((plane0 + p) * Lz + jz) * mt + kt] = acc;
+  }
+}
+
+// ------------------------------------------------------------------------------------------
 // Complex pruned transform along the middle axis of [outer][N][inner] -> [outer][L][inner]
 // ------------------------------------------------------------------------------------------
 template <int M>
@@ -428,6 +524,7 @@ __global__ __launch_bounds__(256) void zt_inv_mfma_kernel(
   float2* V = reinterpret_cast<float2*>(smem);          // [CP][Rz][mt]
   float* CS = smem + 2 * CP * Rz * mt;                  // [2 mt][NT]: cos rows and -sin rows
   float* Wt = CS + 2 * mt * NT;                         // [Cu][CP]
+  float2* TWQ = reinterpret_cast<float2*>(Wt + (ep.u != nullptr ? ep.Cu * CP : 0));   // [Q][Lz]
   const int tid = threadIdx.x;
   const long long slot = blockIdx.x >> 3;
   const int xcd = blockIdx.x & 7;
@@ -462,23 +559,39 @@ __global__ __launch_bounds__(256) void zt_inv_mfma_kernel(
       Wt[idx] = o < Co ? ep.W[o * ep.w_so + i * ep.w_si] : 0.f;
     }
   }
+  for (int idx = tid; idx < Q * Lz; idx += nthr) {
+    const int q = idx / Lz, j = idx - q * Lz;
+    TWQ[idx] = twz[j * Pz + g * Q + q];
+  }
 
-  // z stage: twiddled gather into MZ bins, inverse FFT over n1 (as in the generic kernel)
+  // z stage: twiddled gather into MZ bins, inverse FFT over n1.  The MZ loads of one pass are
+  // independent and issued together; the twiddles of this block's residue classes sit in LDS.
+  __syncthreads();
+  const int mbase = posmod(-kmin, MZ);
+  const int npass = (Lz + MZ - 1) / MZ;
   for (int idx = tid; idx < Co * mt * Q; idx += nthr) {
     const int q = idx % Q;
     const int kt = (idx / Q) % mt;
     const int o = idx / (Q * mt);
-    const int n2 = g * Q + q;
     const float2* src = a + (((b * Co + o) * NxNy + xy) * Lz) * mt + kt;
+    const float2* twq = TWQ + q * Lz;
     float2 gbin[MZ];
 #pragma unroll
-    for (int m = 0; m < MZ; ++m) {
-      float2 acc = make_float2(0.f, 0.f);
-      for (int k = kmin + posmod(m - kmin, MZ); k <= kmax; k += MZ) {
-        const int j = k >= 0 ? k : k + Lz;
-        acc = cfmac(src[j * mt], twz[j * Pz + n2], acc);
+    for (int m = 0; m < MZ; ++m) gbin[m] = make_float2(0.f, 0.f);
+    for (int pass = 0; pass < npass; ++pass) {
+      float2 val[MZ];
+      int jj[MZ];
+#pragma unroll
+      for (int m = 0; m < MZ; ++m) {
+        const int k = kmin + ((m + mbase) & (MZ - 1)) + pass * MZ;
+        const bool ok = k <= kmax;
+        const int j = ok ? (k >= 0 ? k : k + Lz) : 0;
+        jj[m] = j;
+        const float2 v = src[j * mt];
+        val[m] = ok ? v : make_float2(0.f, 0.f);
       }
-      gbin[m] = acc;
+#pragma unroll
+      for (int m = 0; m < MZ; ++m) gbin[m] = cfmac(val[m], twq[jj[m]], gbin[m]);
     }
     fft_reg<MZ, +1>(gbin);
 #pragma unroll
@@ -738,12 +851,37 @@ hipError_t launch_t_table(float2* twt, int Nt, int mt, hipStream_t s) {
   return hipGetLastError();
 }
 
+size_t tz_fast_lds(AxisPlan az, int Nt, int mt, int ppb) {
+  return (size_t)ppb * az.N * (Nt + 4) * 4 + (size_t)ppb * mt * (az.N + 1) * 8 + (size_t)az.L * az.P * 8;
+}
+
 hipError_t launch_tz_fwd(const float* x, float2* out, const float2* twt, const float2* twz,
                          int64_t planes, AxisPlan az, int Nt, int mt, hipStream_t s) {
   if (planes <= 0) return hipSuccess;
+  const bool fast = (Nt == 16 || Nt == 32 || Nt == 64) && (az.M == 8 || az.M == 16 || az.M == 32) &&
+                    (reinterpret_cast<uintptr_t>(x) & 15) == 0 && tz_fast_lds(az, Nt, mt, 1) <= (size_t)kLdsBudget;
+  if (fast) {
+    int ppb = 1;
+    while (ppb * az.N < kThreads && tz_fast_lds(az, Nt, mt, ppb * 2) <= (size_t)kLdsBudget) ppb *= 2;
+    const size_t lds = tz_fast_lds(az, Nt, mt, ppb);
+    const int64_t nblk = (planes + ppb - 1) / ppb;
+    if (nblk > 0x7fffffffLL) return hipErrorInvalidValue;
+#define FNO_TZF(NTV, MZV)                                                                          \
+  hipLaunchKernelGGL((tz_fwd_fast_kernel<NTV, MZV>), dim3((unsigned)nblk), dim3(kThreads), lds, s, \
+                     x, out, twz, (long long)planes, az.N, az.L, az.npos, mt, ppb)
+#define FNO_TZF_M(NTV)                     \
+  do {                                     \
+    if (az.M == 8) FNO_TZF(NTV, 8);        \
+    else if (az.M == 16) FNO_TZF(NTV, 16); \
+    else FNO_TZF(NTV, 32);                 \
+  } while (0)
+    if (Nt == 16) FNO_TZF_M(16); else if (Nt == 32) FNO_TZF_M(32); else FNO_TZF_M(64);
+#undef FNO_TZF_M
+#undef FNO_TZF
+    return hipGetLastError();
+  }
   int ppb = 1;
   // enough rows to occupy the block, within an LDS share that keeps several blocks per CU
-  
   while (ppb * 2 * az.N <= 2 * kThreads && tz_fwd_lds(az, Nt, mt, ppb * 2) <= (size_t)(32 * 1024)) ppb *= 2;
   const size_t lds = tz_fwd_lds(az, Nt, mt, ppb);
   const int64_t nblk = (planes + ppb - 1) / ppb;
@@ -820,7 +958,7 @@ int mfma_q(AxisPlan az, int Nt) {
 
 size_t zt_mfma_lds(AxisPlan az, int Nt, int mt, int Co, int Cu, int q) {
   const int CP = 4 * ((Co + 3) / 4 <= 2 ? 2 : ((Co + 3) / 4 <= 5 ? 5 : 8));
-  return ((size_t)2 * CP * q * az.M * mt + (size_t)2 * mt * Nt + (size_t)Cu * CP) * 4;
+  return ((size_t)2 * CP * q * az.M * mt + (size_t)2 * mt * Nt + (size_t)Cu * CP + (size_t)2 * q * az.L) * 4;
 }
 
 hipError_t launch_zt_inv(const float2* a, float* out, const float2* twt, const float2* twz, int B,
