@@ -24,6 +24,22 @@ __device__ __forceinline__ int posmod(int a, int m) { int r = a % m; return r < 
 __device__ __forceinline__ float gelu_f(float z) {
   return 0.5f * z * (1.0f + erff(z * 0.70710678118654752440f));
 }
+// GELU for the forward epilogue without branches or erff: with x = |z|/sqrt(2),
+//   erf(x) = 1 - (1 + a1 x + ... + a6 x^6)^-16   (Abramowitz & Stegun 7.1.28, |error| <= 3e-7)
+// and z Phi(z) = (z + |z| erf(x)) / 2.  The error it adds to the output is below 2e-7 |z|.
+__device__ __forceinline__ float gelu_fast_f(float z) {
+  const float az = fabsf(z);
+  const float x = az * 0.70710678118654752440f;
+  float p = fmaf(x, 0.0000430638f, 0.0002765672f);
+  p = fmaf(x, p, 0.0001520143f);
+  p = fmaf(x, p, 0.0092705272f);
+  p = fmaf(x, p, 0.0422820123f);
+  p = fmaf(x, p, 0.0705230784f);
+  p = fmaf(x, p, 1.0f);
+  p = p * p; p = p * p; p = p * p; p = p * p;
+  const float erfx = 1.0f - __frcp_rn(p);
+  return 0.5f * fmaf(az, erfx, z);
+}
 __device__ __forceinline__ float gelu_prime_f(float z) {
   const float cdf = 0.5f * (1.0f + erff(z * 0.70710678118654752440f));
   const float pdf = 0.39894228040143267794f * expf(-0.5f * z * z);
@@ -146,26 +162,26 @@ __global__ __launch_bounds__(kThreads) void tz_fwd_kernel(
 // ------------------------------------------------------------------------------------------
 // X[K] = E[K] + w^K O[K],  E = (Z[K] + conj Z[H-K]) / 2,  O = (Z[K] - conj Z[H-K]) / (2i)
 template <int NT, int K>
-__device__ __forceinline__ void rfft_bin(const float2 (&zc)[NT / 2], int mt, float2* __restrict__ tcol, int tstride) {
+__device__ __forceinline__ void rfft_bin(const float2 (&zc)[NT / 2], int mt, float2 (&X)[NT / 2 + 1]) {
   constexpr int H = NT / 2;
   if (K < mt) {
     const float2 zk = zc[bitrev<H>(K % H)];
     const float2 zm = zc[bitrev<H>((H - K) % H)];
     const float2 e = make_float2(0.5f * (zk.x + zm.x), 0.5f * (zk.y - zm.y));
     const float2 od = make_float2(0.5f * (zk.y + zm.y), -0.5f * (zk.x - zm.x));
-    tcol[K * tstride] = cadd(e, mul_root<NT, K, -1>(od));
+    X[K] = cadd(e, mul_root<NT, K, -1>(od));
   }
 }
 
 template <int NT, int... Ks>
-__device__ __forceinline__ void rfft_bins(const float2 (&zc)[NT / 2], int mt, float2* __restrict__ tcol, int tstride,
+__device__ __forceinline__ void rfft_bins(const float2 (&zc)[NT / 2], int mt, float2 (&X)[NT / 2 + 1],
                                           std::integer_sequence<int, Ks...>) {
-  (rfft_bin<NT, Ks>(zc, mt, tcol, tstride), ...);
+  (rfft_bin<NT, Ks>(zc, mt, X), ...);
 }
 
+// Bins 0..mt-1 of the real-input transform of one row of NT floats (16-byte aligned, in LDS).
 template <int NT>
-__device__ __forceinline__ void rfft_row_bins(const float* __restrict__ srow, int mt, float2* __restrict__ tcol,
-                                              int tstride) {
+__device__ __forceinline__ void rfft_row_bins(const float* __restrict__ srow, int mt, float2 (&X)[NT / 2 + 1]) {
   constexpr int H = NT / 2;
   float2 zc[H];
 #pragma unroll
@@ -175,41 +191,51 @@ __device__ __forceinline__ void rfft_row_bins(const float* __restrict__ srow, in
     zc[2 * m4 + 1] = make_float2(v.z, v.w);
   }
   fft_reg<H, -1>(zc);
-  rfft_bins<NT>(zc, mt, tcol, tstride, std::make_integer_sequence<int, H + 1>{});
+  rfft_bins<NT>(zc, mt, X, std::make_integer_sequence<int, H + 1>{});
 }
 
+// One thread per z-row (blockDim.x >= ppb * Nz).  The t-stage results wait in registers over a
+// barrier so the complex tile T can reuse the LDS of the real tile S.
 template <int NT, int MZ>
 __global__ __launch_bounds__(kThreads) void tz_fwd_fast_kernel(
     const float* __restrict__ x, float2* __restrict__ out, const float2* __restrict__ twz,
-    long long planes, int Nz, int Lz, int nposz, int mt, int ppb) {
+    long long planes, int Nz, int Lz, int nposz, int mt, int ppb, int region_floats) {
   HIP_DYNAMIC_SHARED(float, smem)
   const int Pz = Nz / MZ;
   constexpr int sS = NT + 4;                   // row stride of S in floats (keeps float4 alignment)
+  constexpr int H = NT / 2;
   const int sT = Nz + 1;                       // row stride of T in float2
   float* S = smem;                             // [ppb][Nz][sS]
-  float2* T = reinterpret_cast<float2*>(smem + ppb * Nz * sS);   // [ppb][mt][sT]
-  float2* TW = T + ppb * mt * sT;              // [Lz][Pz]
+  float2* T = reinterpret_cast<float2*>(smem); // [ppb][mt][sT], same memory, later
+  float2* TW = reinterpret_cast<float2*>(smem + region_floats);   // [Lz][Pz]
   const int tid = threadIdx.x;
+  const int nthr = blockDim.x;
   const long long plane0 = (long long)blockIdx.x * ppb;
   const int np = (int)min((long long)ppb, planes - plane0);
   const int plane_quads = Nz * (NT / 4);
 
   const float4* src = reinterpret_cast<const float4*>(x + plane0 * Nz * NT);
-  for (int idx = tid; idx < np * plane_quads; idx += kThreads) {
+  for (int idx = tid; idx < np * plane_quads; idx += nthr) {
     const int row = idx / (NT / 4), q4 = idx - row * (NT / 4);
     *reinterpret_cast<float4*>(S + row * sS + 4 * q4) = src[idx];
   }
-  for (int idx = tid; idx < Lz * Pz; idx += kThreads) TW[idx] = twz[idx];
+  for (int idx = tid; idx < Lz * Pz; idx += nthr) TW[idx] = twz[idx];
   __syncthreads();
 
-  for (int row = tid; row < np * Nz; row += kThreads) {
-    const int p = row / Nz, z = row - p * Nz;
-    rfft_row_bins<NT>(S + row * sS, mt, T + (p * mt) * sT + z, sT);
+  const bool live = tid < np * Nz;
+  float2 X[H + 1];
+  if (live) rfft_row_bins<NT>(S + tid * sS, mt, X);
+  __syncthreads();
+  if (live) {
+    const int p = tid / Nz, z = tid - p * Nz;
+#pragma unroll
+    for (int k = 0; k <= H; ++k)
+      if (k < mt) T[(p * mt + k) * sT + z] = X[k];
   }
   __syncthreads();
 
   if constexpr (MZ > 1) {
-    for (int idx = tid; idx < np * mt * Pz; idx += kThreads) {
+    for (int idx = tid; idx < np * mt * Pz; idx += nthr) {
       const int n2 = idx % Pz, col = idx / Pz;
       float2* base = T + col * sT + n2;
       float2 a[MZ];
@@ -222,7 +248,7 @@ __global__ __launch_bounds__(kThreads) void tz_fwd_fast_kernel(
     __syncthreads();
   }
 
-  for (int idx = tid; idx < np * Lz * mt; idx += kThreads) {
+  for (int idx = tid; idx < np * Lz * mt; idx += nthr) {
     const int kt = idx % mt;
     const int jz = (idx / mt) % Lz;
     const int p = idx / (mt * Lz);
@@ -653,7 +679,7 @@ __global__ __launch_bounds__(256) void zt_inv_mfma_kernel(
         float4 zv = make_float4(acc[T][0][r], acc[T][1][r], acc[T][2][r], acc[T][3][r]);
         const long long oidx = (b * Co + o) * Npts + off;
         if (ep.zsave != nullptr) *reinterpret_cast<float4*>(ep.zsave + oidx) = zv;
-        if (ep.act) zv = make_float4(gelu_f(zv.x), gelu_f(zv.y), gelu_f(zv.z), gelu_f(zv.w));
+        if (ep.act) zv = make_float4(gelu_fast_f(zv.x), gelu_fast_f(zv.y), gelu_fast_f(zv.z), gelu_fast_f(zv.w));
         *reinterpret_cast<float4*>(out + oidx) = zv;
       }
     }
@@ -851,24 +877,34 @@ hipError_t launch_t_table(float2* twt, int Nt, int mt, hipStream_t s) {
   return hipGetLastError();
 }
 
+int tz_fast_region(AxisPlan az, int Nt, int mt, int ppb) {
+  const int s_floats = ppb * az.N * (Nt + 4);
+  const int t_floats = 2 * ppb * mt * (az.N + 1);
+  const int r = s_floats > t_floats ? s_floats : t_floats;
+  return (r + 3) & ~3;
+}
+
 size_t tz_fast_lds(AxisPlan az, int Nt, int mt, int ppb) {
-  return (size_t)ppb * az.N * (Nt + 4) * 4 + (size_t)ppb * mt * (az.N + 1) * 8 + (size_t)az.L * az.P * 8;
+  return (size_t)tz_fast_region(az, Nt, mt, ppb) * 4 + (size_t)az.L * az.P * 8;
 }
 
 hipError_t launch_tz_fwd(const float* x, float2* out, const float2* twt, const float2* twz,
                          int64_t planes, AxisPlan az, int Nt, int mt, hipStream_t s) {
   if (planes <= 0) return hipSuccess;
   const bool fast = (Nt == 16 || Nt == 32 || Nt == 64) && (az.M == 8 || az.M == 16 || az.M == 32) &&
-                    (reinterpret_cast<uintptr_t>(x) & 15) == 0 && tz_fast_lds(az, Nt, mt, 1) <= (size_t)kLdsBudget;
+                    az.N <= kThreads && (reinterpret_cast<uintptr_t>(x) & 15) == 0 &&
+                    tz_fast_lds(az, Nt, mt, 1) <= (size_t)kLdsBudget;
   if (fast) {
     int ppb = 1;
-    while (ppb * az.N < kThreads && tz_fast_lds(az, Nt, mt, ppb * 2) <= (size_t)kLdsBudget) ppb *= 2;
+    while (ppb * 2 * az.N <= 128 && tz_fast_lds(az, Nt, mt, ppb * 2) <= (size_t)kLdsBudget) ppb *= 2;
+    const int thr = ((ppb * az.N + 63) / 64) * 64;
     const size_t lds = tz_fast_lds(az, Nt, mt, ppb);
+    const int region = tz_fast_region(az, Nt, mt, ppb);
     const int64_t nblk = (planes + ppb - 1) / ppb;
     if (nblk > 0x7fffffffLL) return hipErrorInvalidValue;
-#define FNO_TZF(NTV, MZV)                                                                          \
-  hipLaunchKernelGGL((tz_fwd_fast_kernel<NTV, MZV>), dim3((unsigned)nblk), dim3(kThreads), lds, s, \
-                     x, out, twz, (long long)planes, az.N, az.L, az.npos, mt, ppb)
+#define FNO_TZF(NTV, MZV)                                                                     \
+  hipLaunchKernelGGL((tz_fwd_fast_kernel<NTV, MZV>), dim3((unsigned)nblk), dim3(thr), lds, s, \
+                     x, out, twz, (long long)planes, az.N, az.L, az.npos, mt, ppb, region)
 #define FNO_TZF_M(NTV)                     \
   do {                                     \
     if (az.M == 8) FNO_TZF(NTV, 8);        \
