@@ -28,6 +28,9 @@ def parse():
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--config", default="cfg4", help="workload name from synth.CONFIGS (block forward)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="only run plain device copies of 4 GiB (reference reading for rocprofv3 --pmc "
+                         "FETCH_SIZE / WRITE_SIZE), then exit")
     ap.add_argument("--traffic-file", default=os.path.join(ROOT, "profiles", "traffic.json"),
                     help="measured HBM bytes per launch of the dominant kernel (from rocprofv3 --pmc)")
     return ap.parse_args()
@@ -75,6 +78,15 @@ def main():
     from paper_2204_01205_amd import binding as B
     from paper_2204_01205_amd import synth
 
+    if args.calibrate_copy:
+        torch.cuda.set_device(0)
+        src = torch.ones(1 << 30, dtype=torch.float32, device="cuda")      # 4 GiB
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        print(json.dumps({"calibrate_copy_bytes_each_way": 4 * (1 << 30), "copies": 3}))
+        return
     cfg = synth.CONFIGS[args.config]
     batch, width, grid, modes = cfg["batch"], cfg["width"], tuple(cfg["grid"]), tuple(cfg["modes"])
     counts = synth.retained_counts(modes)

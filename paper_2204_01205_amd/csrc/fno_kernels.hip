@@ -37,7 +37,7 @@ __device__ __forceinline__ float gelu_fast_f(float z) {
   p = fmaf(x, p, 0.0705230784f);
   p = fmaf(x, p, 1.0f);
   p = p * p; p = p * p; p = p * p; p = p * p;
-  const float erfx = 1.0f - __frcp_rn(p);
+  const float erfx = 1.0f - __builtin_amdgcn_rcpf(p);   // v_rcp_f32, 1 ulp
   return 0.5f * fmaf(az, erfx, z);
 }
 __device__ __forceinline__ float gelu_prime_f(float z) {
@@ -525,7 +525,7 @@ __global__ __launch_bounds__(kThreads) void zt_inv_kernel(
 //     z[o] = b[o] + sum_i W[o][i] u[i]  +  sum_kt ( Re V[o][kt] cos(th) - Im V[o][kt] sin(th) )
 // i.e. the channel-linear term of eq. (2) and the complex-to-real step over t share the
 // accumulator.  v_mfma_f32_4x4x1 (16 independent 4x4 outer products per wave, full fp32) fits
-// it without padding: a lane owns 4 consecutive t of one z-row (one float4 of u and of out);
+// it without padding: a lane owns 2 consecutive t of one z-row (one float2 of u and of out);
 // the 4 lanes of an MFMA block lie in the same row, so they share the A column
 // (W[4T..4T+3][i] or V[4T..4T+3][row][kt]) while each lane brings its own B value (u or the
 // twiddle at its t).  Result register r of tile T is channel 4T+r at the lane's own point.
@@ -535,18 +535,18 @@ __global__ __launch_bounds__(kThreads) void zt_inv_kernel(
 typedef float v4f __attribute__((ext_vector_type(4)));
 
 template <int NT, int MZ, int CT>
-__global__ __launch_bounds__(256) void zt_inv_mfma_kernel(
+__global__ __launch_bounds__(256, (MZ >= 32 || CT >= 8) ? 2 : 3) void zt_inv_mfma_kernel(
     const float2* __restrict__ a, float* __restrict__ out, const float2* __restrict__ twt,
     const float2* __restrict__ twz, int Co, int NxNy, long long ncols, int Nz, int Lz, int nposz,
     int mt, int Q, EpiArgs ep) {
   HIP_DYNAMIC_SHARED(float, smem)
   constexpr int CP = 4 * CT;                 // channels padded to whole MFMA tiles
   constexpr int CI = CP;                     // register file for the u loads
-  constexpr int QPR = NT / 4;                // float4 quads per row
+  constexpr int PPR = NT / 2;                // float2 pairs per row: a lane owns 2 consecutive t
   const int Pz = Nz / MZ;
   const int G = Pz / Q;
   const int Rz = Q * MZ;
-  const int nthr = blockDim.x;               // == Rz * QPR
+  const int nthr = blockDim.x;               // == Rz * PPR
   float2* V = reinterpret_cast<float2*>(smem);          // [CP][Rz][mt]
   float* CS = smem + 2 * CP * Rz * mt;                  // [2 mt][NT]: cos rows and -sin rows
   float* Wt = CS + 2 * mt * NT;                         // [Cu][CP]
@@ -559,21 +559,47 @@ __global__ __launch_bounds__(256) void zt_inv_mfma_kernel(
   if (col >= ncols) return;
   const long long b = col / NxNy;
   const long long xy = col % NxNy;
-  const int quad = tid % QPR;
-  const int row = tid / QPR;
+  const int pair = tid % PPR;
+  const int row = tid / PPR;
   const int z = Pz * (row / Q) + g * Q + (row % Q);
   const long long Npts = (long long)NxNy * Nz * NT;
-  const long long off = (xy * Nz + z) * NT + 4 * quad;
+  const long long off = (xy * Nz + z) * NT + 2 * pair;
   const int kmin = nposz - Lz, kmax = nposz - 1;
   const bool lin = ep.u != nullptr;
+  const int mbase = posmod(-kmin, MZ);
+  const int npass = (Lz + MZ - 1) / MZ;
+  const int nitems = Co * mt * Q;
 
   // u loads go out first so they are in flight during the z stage
-  float4 xv[CI];
+  float2 xv[CI];
   if (lin) {
 #pragma unroll
     for (int i = 0; i < CI; ++i)
-      if (i < ep.Cu) xv[i] = *reinterpret_cast<const float4*>(ep.u + (b * ep.Cu + i) * Npts + off);
+      if (i < ep.Cu) xv[i] = *reinterpret_cast<const float2*>(ep.u + (b * ep.Cu + i) * Npts + off);
   }
+
+  // z stage, first gather: item (o, kt, q) collects the kept z-frequencies of one (channel, kt)
+  // column into MZ bins.  The MZ loads of a pass are independent and issued together.
+  int item = tid;
+  float2 val[MZ];
+  int jj[MZ];
+  const float2* src = a;
+  auto gather = [&](int pass) {
+#pragma unroll
+    for (int m = 0; m < MZ; ++m) {
+      const int k = kmin + ((m + mbase) & (MZ - 1)) + pass * MZ;
+      const bool ok = k <= kmax;
+      const int j = ok ? (k >= 0 ? k : k + Lz) : 0;
+      jj[m] = j;
+      const float2 v = src[j * mt];
+      val[m] = ok ? v : make_float2(0.f, 0.f);
+    }
+  };
+  if (item < nitems) {
+    src = a + (((b * Co + item / (Q * mt)) * NxNy + xy) * Lz) * mt + (item / Q) % mt;
+    gather(0);
+  }
+
   for (int idx = tid; idx < 2 * mt * NT; idx += nthr) {
     const int k = idx / NT, t = idx - k * NT;
     const float2 w = twt[(k >> 1) * NT + t];
@@ -589,52 +615,42 @@ __global__ __launch_bounds__(256) void zt_inv_mfma_kernel(
     const int q = idx / Lz, j = idx - q * Lz;
     TWQ[idx] = twz[j * Pz + g * Q + q];
   }
-
-  // z stage: twiddled gather into MZ bins, inverse FFT over n1.  The MZ loads of one pass are
-  // independent and issued together; the twiddles of this block's residue classes sit in LDS.
+  // channels of the padding tiles: finite values so the unused MFMA rows stay harmless
+  for (int idx = tid; idx < (CP - Co) * Rz * mt; idx += nthr) V[Co * Rz * mt + idx] = make_float2(0.f, 0.f);
   __syncthreads();
-  const int mbase = posmod(-kmin, MZ);
-  const int npass = (Lz + MZ - 1) / MZ;
-  for (int idx = tid; idx < Co * mt * Q; idx += nthr) {
-    const int q = idx % Q;
-    const int kt = (idx / Q) % mt;
-    const int o = idx / (Q * mt);
-    const float2* src = a + (((b * Co + o) * NxNy + xy) * Lz) * mt + kt;
+
+  while (item < nitems) {
+    const int q = item % Q;
+    const int kt = (item / Q) % mt;
+    const int o = item / (Q * mt);
     const float2* twq = TWQ + q * Lz;
     float2 gbin[MZ];
 #pragma unroll
     for (int m = 0; m < MZ; ++m) gbin[m] = make_float2(0.f, 0.f);
     for (int pass = 0; pass < npass; ++pass) {
-      float2 val[MZ];
-      int jj[MZ];
-#pragma unroll
-      for (int m = 0; m < MZ; ++m) {
-        const int k = kmin + ((m + mbase) & (MZ - 1)) + pass * MZ;
-        const bool ok = k <= kmax;
-        const int j = ok ? (k >= 0 ? k : k + Lz) : 0;
-        jj[m] = j;
-        const float2 v = src[j * mt];
-        val[m] = ok ? v : make_float2(0.f, 0.f);
-      }
+      if (pass > 0) gather(pass);
 #pragma unroll
       for (int m = 0; m < MZ; ++m) gbin[m] = cfmac(val[m], twq[jj[m]], gbin[m]);
     }
     fft_reg<MZ, +1>(gbin);
 #pragma unroll
     for (int n1 = 0; n1 < MZ; ++n1) V[((o * Rz) + n1 * Q + q) * mt + kt] = gbin[bitrev<MZ>(n1)];
+    item += nthr;
+    if (item < nitems) {
+      src = a + (((b * Co + item / (Q * mt)) * NxNy + xy) * Lz) * mt + (item / Q) % mt;
+      gather(0);
+    }
   }
-  // channels of the padding tiles: finite values so the unused MFMA rows stay harmless
-  for (int idx = tid; idx < (CP - Co) * Rz * mt; idx += nthr) V[Co * Rz * mt + idx] = make_float2(0.f, 0.f);
   __syncthreads();
 
-  v4f acc[CT][4];
+  v4f acc[CT][2];
 #pragma unroll
   for (int T = 0; T < CT; ++T) {
     v4f init;
 #pragma unroll
     for (int r = 0; r < 4; ++r) init[r] = (ep.bias != nullptr && 4 * T + r < Co) ? ep.bias[4 * T + r] : 0.f;
-#pragma unroll
-    for (int s = 0; s < 4; ++s) acc[T][s] = init;
+    acc[T][0] = init;
+    acc[T][1] = init;
   }
   const int lane4 = tid & 3;
   if (lin) {
@@ -646,27 +662,21 @@ __global__ __launch_bounds__(256) void zt_inv_mfma_kernel(
           const float w = Wt[i * CP + 4 * T + lane4];
           acc[T][0] = __builtin_amdgcn_mfma_f32_4x4x1f32(w, xv[i].x, acc[T][0], 0, 0, 0);
           acc[T][1] = __builtin_amdgcn_mfma_f32_4x4x1f32(w, xv[i].y, acc[T][1], 0, 0, 0);
-          acc[T][2] = __builtin_amdgcn_mfma_f32_4x4x1f32(w, xv[i].z, acc[T][2], 0, 0, 0);
-          acc[T][3] = __builtin_amdgcn_mfma_f32_4x4x1f32(w, xv[i].w, acc[T][3], 0, 0, 0);
         }
       }
     }
   }
   const float2* vlane = V + (lane4 * Rz + row) * mt;
   for (int kt = 0; kt < mt; ++kt) {
-    const float4 c4 = *reinterpret_cast<const float4*>(CS + (2 * kt) * NT + 4 * quad);
-    const float4 s4 = *reinterpret_cast<const float4*>(CS + (2 * kt + 1) * NT + 4 * quad);
+    const float2 c2 = *reinterpret_cast<const float2*>(CS + (2 * kt) * NT + 2 * pair);
+    const float2 s2 = *reinterpret_cast<const float2*>(CS + (2 * kt + 1) * NT + 2 * pair);
 #pragma unroll
     for (int T = 0; T < CT; ++T) {
       const float2 v = vlane[(4 * T * Rz) * mt + kt];
-      acc[T][0] = __builtin_amdgcn_mfma_f32_4x4x1f32(v.x, c4.x, acc[T][0], 0, 0, 0);
-      acc[T][1] = __builtin_amdgcn_mfma_f32_4x4x1f32(v.x, c4.y, acc[T][1], 0, 0, 0);
-      acc[T][2] = __builtin_amdgcn_mfma_f32_4x4x1f32(v.x, c4.z, acc[T][2], 0, 0, 0);
-      acc[T][3] = __builtin_amdgcn_mfma_f32_4x4x1f32(v.x, c4.w, acc[T][3], 0, 0, 0);
-      acc[T][0] = __builtin_amdgcn_mfma_f32_4x4x1f32(v.y, s4.x, acc[T][0], 0, 0, 0);
-      acc[T][1] = __builtin_amdgcn_mfma_f32_4x4x1f32(v.y, s4.y, acc[T][1], 0, 0, 0);
-      acc[T][2] = __builtin_amdgcn_mfma_f32_4x4x1f32(v.y, s4.z, acc[T][2], 0, 0, 0);
-      acc[T][3] = __builtin_amdgcn_mfma_f32_4x4x1f32(v.y, s4.w, acc[T][3], 0, 0, 0);
+      acc[T][0] = __builtin_amdgcn_mfma_f32_4x4x1f32(v.x, c2.x, acc[T][0], 0, 0, 0);
+      acc[T][1] = __builtin_amdgcn_mfma_f32_4x4x1f32(v.x, c2.y, acc[T][1], 0, 0, 0);
+      acc[T][0] = __builtin_amdgcn_mfma_f32_4x4x1f32(v.y, s2.x, acc[T][0], 0, 0, 0);
+      acc[T][1] = __builtin_amdgcn_mfma_f32_4x4x1f32(v.y, s2.y, acc[T][1], 0, 0, 0);
     }
   }
 
@@ -676,11 +686,11 @@ __global__ __launch_bounds__(256) void zt_inv_mfma_kernel(
     for (int r = 0; r < 4; ++r) {
       const int o = 4 * T + r;
       if (o < Co) {
-        float4 zv = make_float4(acc[T][0][r], acc[T][1][r], acc[T][2][r], acc[T][3][r]);
+        float2 zv = make_float2(acc[T][0][r], acc[T][1][r]);
         const long long oidx = (b * Co + o) * Npts + off;
-        if (ep.zsave != nullptr) *reinterpret_cast<float4*>(ep.zsave + oidx) = zv;
-        if (ep.act) zv = make_float4(gelu_fast_f(zv.x), gelu_fast_f(zv.y), gelu_fast_f(zv.z), gelu_fast_f(zv.w));
-        *reinterpret_cast<float4*>(out + oidx) = zv;
+        if (ep.zsave != nullptr) *reinterpret_cast<float2*>(ep.zsave + oidx) = zv;
+        if (ep.act) zv = make_float2(gelu_fast_f(zv.x), gelu_fast_f(zv.y));
+        *reinterpret_cast<float2*>(out + oidx) = zv;
       }
     }
   }
@@ -976,17 +986,17 @@ hipError_t launch_mix_bwd(const float2* xh, const float2* R, const float2* gh, f
 }
 
 // Tile of the matrix-core kernel: Q residue classes whose Rz = Q*M rows times Nt points make
-// 256..1024 points (64..256 threads) and whose Q adjacent rows span at least 128 bytes.
+// 128..512 points (64..256 threads, two points each) and whose Q adjacent rows span at least 128 bytes.
 int mfma_q(AxisPlan az, int Nt) {
   if (Nt != 16 && Nt != 32) return 0;
   if (az.M != 8 && az.M != 16 && az.M != 32) return 0;
   int best = 0, best_score = -1;
   for (int q = 1; q <= az.P; ++q) {
     if (az.P % q) continue;
-    const int thr = q * az.M * Nt / 4;
+    const int thr = q * az.M * Nt / 2;
     if (thr > 256) break;
     if (thr % 64) continue;
-    const int score = (q * Nt >= 32 ? 2 : 0) + (thr >= 128 ? 1 : 0);
+    const int score = (q * Nt >= 32 ? 4 : 0) + (thr >= 256 ? 2 : 0) + (thr >= 128 ? 1 : 0);
     if (score > best_score) { best_score = score; best = q; }
   }
   return best;
@@ -1014,7 +1024,7 @@ hipError_t launch_zt_inv(const float2* a, float* out, const float2* twt, const f
     const int G = az.P / qf;
     const int64_t nblk = ((ncols + 7) / 8) * 8 * G;
     if (nblk > 0x7fffffffLL) return hipErrorInvalidValue;
-    const int thr = qf * az.M * Nt / 4;
+    const int thr = qf * az.M * Nt / 2;
     const size_t lds = zt_mfma_lds(az, Nt, mt, Co, ep.u ? ep.Cu : 0, qf);
 #define FNO_ZTM(NTV, MZV, CTV)                                                                     \
   hipLaunchKernelGGL((zt_inv_mfma_kernel<NTV, MZV, CTV>), dim3((unsigned)nblk), dim3(thr), lds, s, \
