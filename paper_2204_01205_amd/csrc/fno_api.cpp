@@ -29,7 +29,7 @@ struct Plan {
   int64_t K;             // kept modes per (batch, channel)
   int64_t Npts;          // grid points per (batch, channel)
   // workspace offsets in bytes
-  size_t off_twt, off_tw[3], off_a1, off_a2, off_s1, off_s2, off_s3, off_gz, off_part, total;
+  size_t off_ztab, off_twt, off_tw[3], off_a1, off_a2, off_s1, off_s2, off_s3, off_gz, off_part, total;
   int part_blocks;
 };
 
@@ -95,6 +95,7 @@ int make_plan(const fno_desc* d, bool need_block, bool need_bwd_block, Plan* p) 
 
   // workspace
   size_t off = 0;
+  p->off_ztab = off; off = align_up(off + fno::kZtTablesBytes);
   p->off_twt = off; off = align_up(off + (size_t)p->mt * p->Nt * 8);
   for (int a = 0; a < 3; ++a) { p->off_tw[a] = off; off = align_up(off + (size_t)p->ax[a].L * p->ax[a].P * 8); }
   const size_t bc = (size_t)p->B * Cm;
@@ -207,7 +208,7 @@ int inverse_chain(const Plan& p, void* ws, const float2* spec, int C, float* out
   FNO_STAGE(FNO_STAGE_X_INV, s, fno::launch_axis_inv(spec, a2, at<float2>(ws, p.off_tw[0]), bc, p.ax[0], in_x, s));
   FNO_STAGE(FNO_STAGE_Y_INV, s, fno::launch_axis_inv(a2, a1, at<float2>(ws, p.off_tw[1]), bc * p.N[0], p.ax[1], in_y, s));
   FNO_STAGE(FNO_STAGE_ZT_INV, s, fno::launch_zt_inv(a1, out, at<float2>(ws, p.off_twt), at<float2>(ws, p.off_tw[2]), p.B, C,
-                             p.N[0], p.N[1], p.ax[2], p.Nt, p.mt, ep, s));
+                             p.N[0], p.N[1], p.ax[2], p.Nt, p.mt, ep, at<float>(ws, p.off_ztab), s));
   return FNO_OK;
 }
 

@@ -50,9 +50,10 @@ struct Epilogue {
 };
 
 // Inverse (z, t) of a[B*Co planes][Lz][mt] plus epilogue  out = act(ys + W u + bias).
+// `tables` is kZtTablesBytes of scratch (16-byte aligned) for the kernel's per-call tables.
 hipError_t launch_zt_inv(const float2* a, float* out, const float2* twt, const float2* twz,
                          int B, int Co, int Nx, int Ny, AxisPlan az, int Nt, int mt,
-                         Epilogue ep, hipStream_t s);
+                         Epilogue ep, float* tables, hipStream_t s);
 
 // gz = g * act'(z) (g = gout or the MSE gradient against a target), written to gz_out;
 // per-block partial sums of gb[o] and gW[o][i] into part[nblk][Co*Ci + Co] (double).
@@ -73,6 +74,7 @@ hipError_t launch_pointwise_mlp2(int B, int Ci, int H, int Co, int64_t np, const
 constexpr int kMaxFftM = 32;        // largest in-register FFT
 constexpr int kMaxCo = 32;          // accumulator file of the epilogue
 constexpr int kLdsBudget = 60 * 1024;
+constexpr size_t kZtTablesBytes = 512 * 1024;
 bool tz_fwd_fits(AxisPlan az, int Nt, int mt);
 bool zt_inv_fits(AxisPlan az, int Nt, int mt, int Co);
 bool axis_fits(AxisPlan ax);

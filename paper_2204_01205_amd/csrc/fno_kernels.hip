@@ -14,6 +14,9 @@
 
 namespace fno {
 
+unsigned long long* g_dbg = nullptr;
+extern "C" void fno_debug_set(unsigned long long* p) { g_dbg = p; }
+
 namespace {
 
 constexpr int kThreads = 256;
@@ -422,6 +425,7 @@ __global__ __launch_bounds__(kThreads) void mix_bwd_kernel(
 // ------------------------------------------------------------------------------------------
 struct EpiArgs {
   const float* u; int Cu; const float* W; int w_so, w_si; const float* bias; float* zsave; int act;
+  unsigned long long* dbg;
 };
 
 template <int MZ, int CO>
@@ -520,180 +524,299 @@ __global__ __launch_bounds__(kThreads) void zt_inv_kernel(
 }
 
 // ------------------------------------------------------------------------------------------
-// The same stage for t-lengths that are multiples of 16, with the two dense contractions on
-// the matrix cores.  Per grid point the pre-activation is one inner product of length Cu + 2 mt:
+// The same stage for t-lengths 16 and 32, with the two dense contractions on the matrix cores.
+// Per grid point the pre-activation is one inner product of length Cu + 2 mt:
 //     z[o] = b[o] + sum_i W[o][i] u[i]  +  sum_kt ( Re V[o][kt] cos(th) - Im V[o][kt] sin(th) )
 // i.e. the channel-linear term of eq. (2) and the complex-to-real step over t share the
 // accumulator.  v_mfma_f32_4x4x1 (16 independent 4x4 outer products per wave, full fp32) fits
-// it without padding: a lane owns 2 consecutive t of one z-row (one float2 of u and of out);
-// the 4 lanes of an MFMA block lie in the same row, so they share the A column
-// (W[4T..4T+3][i] or V[4T..4T+3][row][kt]) while each lane brings its own B value (u or the
-// twiddle at its t).  Result register r of tile T is channel 4T+r at the lane's own point.
+// it without padding.  An MFMA block is 4 consecutive t of one z-row ("quad") times 4
+// channels: lane 4b+i supplies the A value at t = 4 quad + i (u of the current input channel,
+// or the twiddle), lane 4b+j supplies the B value of channel 4T+j (W[4T+j][i] or V[4T+j][row][kt]),
+// and lane 4b+j receives, in its four result registers, channel 4T+j at the quad's four t:
+// one float4 of the output.  A lane serves two quads (slots).
 // Blocks that share a (b,nx,ny) column are placed on one XCD so the column's spectrum tile
 // is fetched into that XCD's L2 once.
 // ------------------------------------------------------------------------------------------
 typedef float v4f __attribute__((ext_vector_type(4)));
 
-template <int NT, int MZ, int CT>
+
+
+// Tables of the matrix-core inverse kernel, one blob per residue group g in the kernel's LDS
+// layout: cos / -sin rows [2 mt][NT], W transposed and padded [Cu][CP], z twiddles [Q][Lz].
+__global__ void zt_tables_kernel(float* __restrict__ blob, const float2* __restrict__ twt,
+                                 const float2* __restrict__ twz, const float* __restrict__ W, int w_so,
+                                 int w_si, int Co, int Cu, int CP, int mt, int NT, int Lz, int Pz, int Q,
+                                 int blob_floats) {
+  const int g = blockIdx.x;
+  float* dst = blob + (long long)g * blob_floats;
+  const int n_cs = 2 * mt * NT, n_wt = (W != nullptr) ? Cu * CP : 0, n_tw = 2 * Q * Lz;
+  for (int idx = threadIdx.x; idx < blob_floats; idx += blockDim.x) {
+    float v = 0.f;
+    if (idx < n_cs) {
+      const int k = idx / NT, t = idx - k * NT;
+      const float2 w = twt[(k >> 1) * NT + t];
+      v = (k & 1) ? w.y : w.x;
+    } else if (idx < n_cs + n_wt) {
+      const int e = idx - n_cs;
+      const int i = e / CP, o = e - i * CP;
+      v = o < Co ? W[o * w_so + i * w_si] : 0.f;
+    } else if (idx < n_cs + n_wt + n_tw) {
+      const int e = idx - n_cs - n_wt;
+      const int c = e >> 1, q = c / Lz, j = c - q * Lz;
+      const float2 w = twz[j * Pz + g * Q + q];
+      v = (e & 1) ? w.y : w.x;
+    }
+    dst[idx] = v;
+  }
+}
+
+#define FNO_TS(n) do { if (ep.dbg != nullptr && (tid & 63) == 0) { unsigned long long t_ = clock64(); if (tid == 0) { atomicAdd(ep.dbg + (n), t_ - tprev); } tprev = t_; } } while (0)
+// Launch: grid (8 * G * ceil(NxNy / 8), B), 256 threads.  Q and G are powers of two (shifts
+// instead of divisions); inv_mt = ceil(2^16 / mt) turns the division by mt into a multiply.
+// FULL means Co == 4 CT and (no linear term or Cu == 4 CT): channel guards vanish at compile time.
+template <int NT, int MZ, int CT, bool FULL>
 __global__ __launch_bounds__(256, (MZ >= 32 || CT >= 8) ? 2 : 3) void zt_inv_mfma_kernel(
     const float2* __restrict__ a, float* __restrict__ out, const float2* __restrict__ twt,
-    const float2* __restrict__ twz, int Co, int NxNy, long long ncols, int Nz, int Lz, int nposz,
-    int mt, int Q, EpiArgs ep) {
+    const float2* __restrict__ twz, int Co_rt, int NxNy, int Nz, int Lz, int nposz, int mt,
+    int qshift, int gshift, int inv_mt, int region_floats, unsigned inv_ch4, const float* __restrict__ blob, int blob_floats, EpiArgs ep) {
   HIP_DYNAMIC_SHARED(float, smem)
   constexpr int CP = 4 * CT;                 // channels padded to whole MFMA tiles
-  constexpr int CI = CP;                     // register file for the u loads
-  constexpr int PPR = NT / 2;                // float2 pairs per row: a lane owns 2 consecutive t
+  constexpr int CI = CP;                     // bound of the input-channel loop
+  constexpr int QPR = NT / 4;                // quads per row
+  constexpr int RPW = 32 / QPR;              // rows per wave: 16 MFMA blocks x 2 slots = 32 quads
+  constexpr int Rz = 4 * RPW;                // rows per tile (4 waves)
+  const int Co = FULL ? CP : Co_rt;
+  const int Cu = FULL ? CI : ep.Cu;
+  const int Q = 1 << qshift;
   const int Pz = Nz / MZ;
-  const int G = Pz / Q;
-  const int Rz = Q * MZ;
-  const int nthr = blockDim.x;               // == Rz * PPR
-  float2* V = reinterpret_cast<float2*>(smem);          // [CP][Rz][mt]
-  float* CS = smem + 2 * CP * Rz * mt;                  // [2 mt][NT]: cos rows and -sin rows
+  constexpr int nthr = 256;
+  // LDS: the column's spectrum tile A [Co][Lz][mt] (complex), staged by LDS-direct loads; once
+  // every z-stage item has read it, the same memory holds V [CP][Rz][mt].  Then the tables.
+  float2* A = reinterpret_cast<float2*>(smem);
+  float2* V = reinterpret_cast<float2*>(smem);
+  float* CS = smem + region_floats;                     // [2 mt][NT]: cos rows and -sin rows
   float* Wt = CS + 2 * mt * NT;                         // [Cu][CP]
-  float2* TWQ = reinterpret_cast<float2*>(Wt + (ep.u != nullptr ? ep.Cu * CP : 0));   // [Q][Lz]
-  const int tid = threadIdx.x;
-  const long long slot = blockIdx.x >> 3;
-  const int xcd = blockIdx.x & 7;
-  const long long col = (slot / G) * 8 + xcd;
-  const int g = (int)(slot % G);
-  if (col >= ncols) return;
-  const long long b = col / NxNy;
-  const long long xy = col % NxNy;
-  const int pair = tid % PPR;
-  const int row = tid / PPR;
-  const int z = Pz * (row / Q) + g * Q + (row % Q);
-  const long long Npts = (long long)NxNy * Nz * NT;
-  const long long off = (xy * Nz + z) * NT + 2 * pair;
-  const int kmin = nposz - Lz, kmax = nposz - 1;
   const bool lin = ep.u != nullptr;
+  float2* TWQ = reinterpret_cast<float2*>(Wt + (lin ? Cu * CP : 0));   // [Q][Lz]
+  const int tid = threadIdx.x;
+  const int xcd = blockIdx.x & 7;
+  const int slot_id = blockIdx.x >> 3;
+  const int xy = ((slot_id >> gshift) << 3) + xcd;
+  const int g = slot_id & ((1 << gshift) - 1);
+  if (xy >= NxNy) return;
+  unsigned long long tprev = clock64();
+  const long long b = blockIdx.y;
+  const int lane = tid & 63, wave = tid >> 6;
+  const int j4 = lane & 3;                    // t within the quad (A side) / channel within the tile (B, D side)
+  const int blk = lane >> 2;
+  const int quad = blk % QPR;                 // same for both slots because 16 % QPR == 0
+  int rowt[2];                                // tile row of each slot
+  long long poff[2];                          // offset of the quad's first point inside a channel slab
+#pragma unroll
+  for (int sl = 0; sl < 2; ++sl) {
+    rowt[sl] = wave * RPW + (sl * 16 + blk) / QPR;
+    const int z = Pz * (rowt[sl] >> qshift) + (g << qshift) + (rowt[sl] & (Q - 1));
+    poff[sl] = ((long long)xy * Nz + z) * NT + 4 * quad;
+  }
+  const long long Npts = (long long)NxNy * Nz * NT;
+  const int kmin = nposz - Lz, kmax = nposz - 1;
   const int mbase = posmod(-kmin, MZ);
-  const int npass = (Lz + MZ - 1) / MZ;
-  const int nitems = Co * mt * Q;
+  const int nitems = (Co * mt) << qshift;
 
-  // u loads go out first so they are in flight during the z stage
-  float2 xv[CI];
-  if (lin) {
-#pragma unroll
-    for (int i = 0; i < CI; ++i)
-      if (i < ep.Cu) xv[i] = *reinterpret_cast<const float2*>(ep.u + (b * ep.Cu + i) * Npts + off);
+  // tables: one contiguous blob per residue group, prepared by zt_tables_kernel in the LDS layout
+  {
+    const float* bsrc = blob + (long long)g * blob_floats;
+    for (int c0 = wave * 256; c0 < blob_floats; c0 += 1024)
+      __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(bsrc + c0 + 4 * lane),
+                                       (__attribute__((address_space(3))) void*)(CS + c0), 16, 0, 0);
   }
-
-  // z stage, first gather: item (o, kt, q) collects the kept z-frequencies of one (channel, kt)
-  // column into MZ bins.  The MZ loads of a pass are independent and issued together.
-  int item = tid;
-  float2 val[MZ];
-  int jj[MZ];
-  const float2* src = a;
-  auto gather = [&](int pass) {
-#pragma unroll
-    for (int m = 0; m < MZ; ++m) {
-      const int k = kmin + ((m + mbase) & (MZ - 1)) + pass * MZ;
-      const bool ok = k <= kmax;
-      const int j = ok ? (k >= 0 ? k : k + Lz) : 0;
-      jj[m] = j;
-      const float2 v = src[j * mt];
-      val[m] = ok ? v : make_float2(0.f, 0.f);
-    }
-  };
-  if (item < nitems) {
-    src = a + (((b * Co + item / (Q * mt)) * NxNy + xy) * Lz) * mt + (item / Q) % mt;
-    gather(0);
-  }
-
-  for (int idx = tid; idx < 2 * mt * NT; idx += nthr) {
-    const int k = idx / NT, t = idx - k * NT;
-    const float2 w = twt[(k >> 1) * NT + t];
-    CS[idx] = (k & 1) ? w.y : w.x;
-  }
-  if (lin) {
-    for (int idx = tid; idx < ep.Cu * CP; idx += nthr) {
-      const int i = idx / CP, o = idx - i * CP;
-      Wt[idx] = o < Co ? ep.W[o * ep.w_so + i * ep.w_si] : 0.f;
+  asm volatile("" ::: "memory");    // keep the issue order: tables, tile, u (the wait below counts on it)
+  // the spectrum tile goes straight to LDS: 16 bytes per lane, 1 KiB per wave instruction;
+  // lanes past the end re-read the last piece into the padding of the region
+  {
+    const int per_ch4 = (Lz * mt) >> 1;                  // float4 pieces per channel
+    const int nf4 = Co * per_ch4;
+    const float2* abase = a + ((b * Co) * NxNy + xy) * (long long)(Lz * mt);
+    const long long astride = (long long)NxNy * Lz * mt; // float2 between channels
+    for (int c0 = wave * 64; c0 < nf4; c0 += 256) {
+      int f = c0 + lane;
+      f = f < nf4 ? f : nf4 - 1;
+      const int o = (int)__umulhi((unsigned)f, inv_ch4);
+      const int r = f - o * per_ch4;
+      const float2* gsrc = abase + o * astride + 2 * r;
+      __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)gsrc,
+                                       (__attribute__((address_space(3))) void*)(smem + 4 * c0), 16, 0, 0);
     }
   }
-  for (int idx = tid; idx < Q * Lz; idx += nthr) {
-    const int q = idx / Lz, j = idx - q * Lz;
-    TWQ[idx] = twz[j * Pz + g * Q + q];
+
+  asm volatile("" ::: "memory");
+  // u loads last so they stay in flight during the z stage: lane 4b+i takes t = 4 quad + i
+  float xv[CI][2];
+  if (lin) {
+    const float* up = ep.u + (b * Cu) * Npts + j4;
+#pragma unroll
+    for (int i = 0; i < CI; ++i) {
+      if (FULL || i < Cu) {
+        xv[i][0] = up[i * Npts + poff[0]];
+        xv[i][1] = up[i * Npts + poff[1]];
+      }
+    }
   }
-  // channels of the padding tiles: finite values so the unused MFMA rows stay harmless
-  for (int idx = tid; idx < (CP - Co) * Rz * mt; idx += nthr) V[Co * Rz * mt + idx] = make_float2(0.f, 0.f);
+  asm volatile("" ::: "memory");
+  // wait for the table blob and the tile, not for the u loads (they were issued after them;
+  // the counter retires in order).  vmcnt sits in bits 3:0 and 15:14 of the immediate.
+  if constexpr (FULL && 2 * CI < 64) {
+    constexpr int n = 2 * CI;
+    if (lin) __builtin_amdgcn_s_waitcnt(((n >> 4) << 14) | 0x0F70 | (n & 15));
+    else __builtin_amdgcn_s_waitcnt(0x0F70);
+  } else {
+    __builtin_amdgcn_s_waitcnt(0x0F70);
+  }
+  FNO_TS(0);
   __syncthreads();
+  FNO_TS(1);
 
-  while (item < nitems) {
-    const int q = item % Q;
-    const int kt = (item / Q) % mt;
-    const int o = item / (Q * mt);
-    const float2* twq = TWQ + q * Lz;
-    float2 gbin[MZ];
+  // z stage: item (o, kt, q) collects the kept z-frequencies of one (channel, kt) column with
+  // their twiddles into MZ bins; an inverse FFT over n1 gives the rows z = Pz n1 + n2.  At most
+  // kZItems items per thread; their results wait in registers until every item has read A.
+  constexpr int kZItems = 2;
+  float2 gres[kZItems][MZ];
 #pragma unroll
-    for (int m = 0; m < MZ; ++m) gbin[m] = make_float2(0.f, 0.f);
-    for (int pass = 0; pass < npass; ++pass) {
-      if (pass > 0) gather(pass);
-#pragma unroll
-      for (int m = 0; m < MZ; ++m) gbin[m] = cfmac(val[m], twq[jj[m]], gbin[m]);
-    }
-    fft_reg<MZ, +1>(gbin);
-#pragma unroll
-    for (int n1 = 0; n1 < MZ; ++n1) V[((o * Rz) + n1 * Q + q) * mt + kt] = gbin[bitrev<MZ>(n1)];
-    item += nthr;
+  for (int it = 0; it < kZItems; ++it) {
+    const int item = tid + it * 256;
     if (item < nitems) {
-      src = a + (((b * Co + item / (Q * mt)) * NxNy + xy) * Lz) * mt + (item / Q) % mt;
-      gather(0);
+      const int q = item & (Q - 1);
+      const int r = item >> qshift;
+      const int o = (r * inv_mt) >> 16;
+      const int kt = r - o * mt;
+      const float2* asrc = A + o * (Lz * mt) + kt;
+      const float2* twq = TWQ + q * Lz;
+#pragma unroll
+      for (int m = 0; m < MZ; ++m) {
+        float2 accb = make_float2(0.f, 0.f);
+        for (int k = kmin + ((m + mbase) & (MZ - 1)); k <= kmax; k += MZ) {
+          const int j = k >= 0 ? k : k + Lz;
+          accb = cfmac(asrc[j * mt], twq[j], accb);
+        }
+        gres[it][m] = accb;
+      }
+      fft_reg<MZ, +1>(gres[it]);
     }
   }
+  FNO_TS(2);
   __syncthreads();
+#pragma unroll
+  for (int it = 0; it < kZItems; ++it) {
+    const int item = tid + it * 256;
+    if (item < nitems) {
+      const int q = item & (Q - 1);
+      const int r = item >> qshift;
+      const int o = (r * inv_mt) >> 16;
+      const int kt = r - o * mt;
+      float2* vdst = V + ((o * Rz) + q) * mt + kt;
+      const int vstep = mt << qshift;
+#pragma unroll
+      for (int n1 = 0; n1 < MZ; ++n1) vdst[n1 * vstep] = gres[it][bitrev<MZ>(n1)];
+    }
+  }
+  if (!FULL) {
+    // channels of the padding tiles: finite values so the unused MFMA columns stay harmless
+    for (int idx = tid; idx < (CP - Co) * Rz * mt; idx += nthr) V[Co * Rz * mt + idx] = make_float2(0.f, 0.f);
+  }
+  __syncthreads();
+  FNO_TS(3);
 
   v4f acc[CT][2];
 #pragma unroll
   for (int T = 0; T < CT; ++T) {
-    v4f init;
-#pragma unroll
-    for (int r = 0; r < 4; ++r) init[r] = (ep.bias != nullptr && 4 * T + r < Co) ? ep.bias[4 * T + r] : 0.f;
+    const float bv = (ep.bias != nullptr && (FULL || 4 * T + j4 < Co)) ? ep.bias[4 * T + j4] : 0.f;
+    const v4f init = {bv, bv, bv, bv};
     acc[T][0] = init;
     acc[T][1] = init;
   }
-  const int lane4 = tid & 3;
   if (lin) {
+    constexpr int IB = 4;                       // input channels per batch of LDS reads
 #pragma unroll
-    for (int i = 0; i < CI; ++i) {
-      if (i < ep.Cu) {
+    for (int i0 = 0; i0 < CI; i0 += IB) {
+      float wv[IB][CT];
 #pragma unroll
-        for (int T = 0; T < CT; ++T) {
-          const float w = Wt[i * CP + 4 * T + lane4];
-          acc[T][0] = __builtin_amdgcn_mfma_f32_4x4x1f32(w, xv[i].x, acc[T][0], 0, 0, 0);
-          acc[T][1] = __builtin_amdgcn_mfma_f32_4x4x1f32(w, xv[i].y, acc[T][1], 0, 0, 0);
+      for (int ii = 0; ii < IB; ++ii)
+#pragma unroll
+        for (int T = 0; T < CT; ++T)
+          wv[ii][T] = (FULL || i0 + ii < Cu) ? Wt[(i0 + ii) * CP + 4 * T + j4] : 0.f;
+#pragma unroll
+      for (int ii = 0; ii < IB; ++ii) {
+        if (FULL || i0 + ii < Cu) {
+#pragma unroll
+          for (int T = 0; T < CT; ++T) {
+            acc[T][0] = __builtin_amdgcn_mfma_f32_4x4x1f32(xv[i0 + ii][0], wv[ii][T], acc[T][0], 0, 0, 0);
+            acc[T][1] = __builtin_amdgcn_mfma_f32_4x4x1f32(xv[i0 + ii][1], wv[ii][T], acc[T][1], 0, 0, 0);
+          }
         }
       }
     }
   }
-  const float2* vlane = V + (lane4 * Rz + row) * mt;
+  FNO_TS(4);
+  const float* cs_lane = CS + 4 * quad + j4;
+  const float2* v0 = V + (j4 * Rz + rowt[0]) * mt;
+  const float2* v1 = V + (j4 * Rz + rowt[1]) * mt;
   for (int kt = 0; kt < mt; ++kt) {
-    const float2 c2 = *reinterpret_cast<const float2*>(CS + (2 * kt) * NT + 2 * pair);
-    const float2 s2 = *reinterpret_cast<const float2*>(CS + (2 * kt + 1) * NT + 2 * pair);
+    const float c = cs_lane[(2 * kt) * NT];
+    const float sn = cs_lane[(2 * kt + 1) * NT];
+    float2 va[CT], vb[CT];
 #pragma unroll
     for (int T = 0; T < CT; ++T) {
-      const float2 v = vlane[(4 * T * Rz) * mt + kt];
-      acc[T][0] = __builtin_amdgcn_mfma_f32_4x4x1f32(v.x, c2.x, acc[T][0], 0, 0, 0);
-      acc[T][1] = __builtin_amdgcn_mfma_f32_4x4x1f32(v.x, c2.y, acc[T][1], 0, 0, 0);
-      acc[T][0] = __builtin_amdgcn_mfma_f32_4x4x1f32(v.y, s2.x, acc[T][0], 0, 0, 0);
-      acc[T][1] = __builtin_amdgcn_mfma_f32_4x4x1f32(v.y, s2.y, acc[T][1], 0, 0, 0);
+      va[T] = v0[(4 * T * Rz) * mt + kt];
+      vb[T] = v1[(4 * T * Rz) * mt + kt];
+    }
+#pragma unroll
+    for (int T = 0; T < CT; ++T) {
+      acc[T][0] = __builtin_amdgcn_mfma_f32_4x4x1f32(c, va[T].x, acc[T][0], 0, 0, 0);
+      acc[T][1] = __builtin_amdgcn_mfma_f32_4x4x1f32(c, vb[T].x, acc[T][1], 0, 0, 0);
+      acc[T][0] = __builtin_amdgcn_mfma_f32_4x4x1f32(sn, va[T].y, acc[T][0], 0, 0, 0);
+      acc[T][1] = __builtin_amdgcn_mfma_f32_4x4x1f32(sn, vb[T].y, acc[T][1], 0, 0, 0);
     }
   }
 
+  FNO_TS(5);
+  // lane 4b+j now holds channel 4T+j at the four t of each of its two quads
+  float* op = out + (b * Co + j4) * Npts;
+  if (ep.zsave != nullptr) {
+    float* zp = ep.zsave + (b * Co + j4) * Npts;
 #pragma unroll
-  for (int T = 0; T < CT; ++T) {
+    for (int T = 0; T < CT; ++T) {
+      if (FULL || 4 * T + j4 < Co) {
 #pragma unroll
-    for (int r = 0; r < 4; ++r) {
-      const int o = 4 * T + r;
-      if (o < Co) {
-        float2 zv = make_float2(acc[T][0][r], acc[T][1][r]);
-        const long long oidx = (b * Co + o) * Npts + off;
-        if (ep.zsave != nullptr) *reinterpret_cast<float2*>(ep.zsave + oidx) = zv;
-        if (ep.act) zv = make_float2(gelu_fast_f(zv.x), gelu_fast_f(zv.y));
-        *reinterpret_cast<float2*>(out + oidx) = zv;
+        for (int sl = 0; sl < 2; ++sl)
+          *reinterpret_cast<float4*>(zp + (4 * T) * Npts + poff[sl]) =
+              make_float4(acc[T][sl][0], acc[T][sl][1], acc[T][sl][2], acc[T][sl][3]);
       }
     }
   }
+  if (ep.act) {
+#pragma unroll
+    for (int T = 0; T < CT; ++T) {
+      if (FULL || 4 * T + j4 < Co) {
+#pragma unroll
+        for (int sl = 0; sl < 2; ++sl)
+          *reinterpret_cast<float4*>(op + (4 * T) * Npts + poff[sl]) =
+              make_float4(gelu_fast_f(acc[T][sl][0]), gelu_fast_f(acc[T][sl][1]),
+                          gelu_fast_f(acc[T][sl][2]), gelu_fast_f(acc[T][sl][3]));
+      }
+    }
+  } else {
+#pragma unroll
+    for (int T = 0; T < CT; ++T) {
+      if (FULL || 4 * T + j4 < Co) {
+#pragma unroll
+        for (int sl = 0; sl < 2; ++sl)
+          *reinterpret_cast<float4*>(op + (4 * T) * Npts + poff[sl]) =
+              make_float4(acc[T][sl][0], acc[T][sl][1], acc[T][sl][2], acc[T][sl][3]);
+      }
+    }
+  }
+  FNO_TS(6);
+  if (ep.dbg != nullptr && tid == 0) atomicAdd(ep.dbg + 7, 1ull);
 }
 
 // ------------------------------------------------------------------------------------------
@@ -871,7 +994,9 @@ size_t zt_mfma_lds(AxisPlan az, int Nt, int mt, int Co, int Cu, int q);
 bool zt_mfma_fits(AxisPlan az, int Nt, int mt, int Co, int Cu) {
   const int q = mfma_q(az, Nt);
   const int CT = (Co + 3) / 4 <= 2 ? 2 : ((Co + 3) / 4 <= 5 ? 5 : 8);
-  return q > 0 && Co <= kMaxCo && Cu <= 4 * CT && zt_mfma_lds(az, Nt, mt, Co, Cu, q) <= (size_t)(64 * 1024);
+  // the tile is staged in 16-byte pieces (L * mt even) and a thread owns at most two z-stage items
+  return q > 0 && q * az.L <= 512 && (az.L * mt) % 2 == 0 && Co * mt * q <= 512 && Co <= kMaxCo &&
+         Cu <= 4 * CT && zt_mfma_lds(az, Nt, mt, Co, Cu, q) <= (size_t)(80 * 1024);
 }
 
 hipError_t launch_axis_table(float2* tw, AxisPlan ax, hipStream_t s) {
@@ -990,50 +1115,75 @@ hipError_t launch_mix_bwd(const float2* xh, const float2* R, const float2* gh, f
 int mfma_q(AxisPlan az, int Nt) {
   if (Nt != 16 && Nt != 32) return 0;
   if (az.M != 8 && az.M != 16 && az.M != 32) return 0;
-  int best = 0, best_score = -1;
-  for (int q = 1; q <= az.P; ++q) {
-    if (az.P % q) continue;
-    const int thr = q * az.M * Nt / 2;
-    if (thr > 256) break;
-    if (thr % 64) continue;
-    const int score = (q * Nt >= 32 ? 4 : 0) + (thr >= 256 ? 2 : 0) + (thr >= 128 ? 1 : 0);
-    if (score > best_score) { best_score = score; best = q; }
-  }
-  return best;
+  if (az.P & (az.P - 1)) return 0;                 // residue-class count must be a power of two
+  const int rz = 4 * (32 / (Nt / 4));              // rows per tile: 16 for Nt = 32, 32 for Nt = 16
+  if (rz % az.M) return 0;
+  const int q = rz / az.M;
+  if (q > az.P) return 0;
+  return q;
+}
+
+int ilog2(int v) { int l = 0; while ((1 << l) < v) ++l; return l; }
+
+// floats of the region shared by the spectrum tile (rounded up to whole 1 KiB wave loads) and V
+int zt_mfma_region(AxisPlan az, int mt, int Co, int q) {
+  const int CT = (Co + 3) / 4 <= 2 ? 2 : ((Co + 3) / 4 <= 5 ? 5 : 8);
+  const int a_floats = ((Co * az.L * mt * 2 + 255) / 256) * 256;
+  const int v_floats = 2 * 4 * CT * q * az.M * mt;
+  return a_floats > v_floats ? a_floats : v_floats;
+}
+
+int zt_mfma_blob(AxisPlan az, int Nt, int mt, int Co, int Cu, int q) {
+  const int CP = 4 * ((Co + 3) / 4 <= 2 ? 2 : ((Co + 3) / 4 <= 5 ? 5 : 8));
+  return ((2 * mt * Nt + Cu * CP + 2 * q * az.L + 255) / 256) * 256;      // whole 1 KiB wave loads
 }
 
 size_t zt_mfma_lds(AxisPlan az, int Nt, int mt, int Co, int Cu, int q) {
-  const int CP = 4 * ((Co + 3) / 4 <= 2 ? 2 : ((Co + 3) / 4 <= 5 ? 5 : 8));
-  return ((size_t)2 * CP * q * az.M * mt + (size_t)2 * mt * Nt + (size_t)Cu * CP + (size_t)2 * q * az.L) * 4;
+  return ((size_t)zt_mfma_region(az, mt, Co, q) + (size_t)zt_mfma_blob(az, Nt, mt, Co, Cu, q)) * 4;
 }
 
 hipError_t launch_zt_inv(const float2* a, float* out, const float2* twt, const float2* twz, int B,
                          int Co, int Nx, int Ny, AxisPlan az, int Nt, int mt, Epilogue ep,
-                         hipStream_t s) {
+                         float* tables, hipStream_t s) {
   const int64_t ncols = (int64_t)B * Nx * Ny;
   if (ncols <= 0) return hipSuccess;
   if (Co > kMaxCo) return hipErrorInvalidValue;
-  EpiArgs e{ep.u, ep.Cu, ep.W, ep.w_so, ep.w_si, ep.bias, ep.zsave, ep.act};
+  EpiArgs e{ep.u, ep.Cu, ep.W, ep.w_so, ep.w_si, ep.bias, ep.zsave, ep.act, g_dbg};
   const int NxNy = Nx * Ny;
   const int CT = (Co + 3) / 4 <= 2 ? 2 : ((Co + 3) / 4 <= 5 ? 5 : 8);
   const int qf = mfma_q(az, Nt);
   const bool aligned = ((reinterpret_cast<uintptr_t>(out) | reinterpret_cast<uintptr_t>(ep.u) |
                          reinterpret_cast<uintptr_t>(ep.zsave)) & 15) == 0;
-  if (qf > 0 && aligned && (ep.u == nullptr || ep.Cu <= 4 * CT) &&
-      zt_mfma_lds(az, Nt, mt, Co, ep.u ? ep.Cu : 0, qf) <= (size_t)(64 * 1024)) {
+  if (qf > 0 && aligned && zt_mfma_fits(az, Nt, mt, Co, ep.u ? ep.Cu : 0) &&
+      ((reinterpret_cast<uintptr_t>(a) | reinterpret_cast<uintptr_t>(tables)) & 15) == 0) {
     const int G = az.P / qf;
-    const int64_t nblk = ((ncols + 7) / 8) * 8 * G;
-    if (nblk > 0x7fffffffLL) return hipErrorInvalidValue;
-    const int thr = qf * az.M * Nt / 2;
+    const int64_t gx = (int64_t)((NxNy + 7) / 8) * 8 * G;
+    if (gx > 0x7fffffffLL || B > 65535 || Co * mt > 7000) return hipErrorInvalidValue;
+    const int thr = 256;
     const size_t lds = zt_mfma_lds(az, Nt, mt, Co, ep.u ? ep.Cu : 0, qf);
-#define FNO_ZTM(NTV, MZV, CTV)                                                                     \
-  hipLaunchKernelGGL((zt_inv_mfma_kernel<NTV, MZV, CTV>), dim3((unsigned)nblk), dim3(thr), lds, s, \
-                     a, out, twt, twz, Co, NxNy, (long long)ncols, az.N, az.L, az.npos, mt, qf, e)
+    const int inv_mt = (65536 + mt - 1) / mt;
+    const unsigned per_ch4 = (unsigned)(az.L * mt) / 2;
+    const unsigned inv_ch4 = (unsigned)((0x100000000ULL + per_ch4 - 1) / per_ch4);
+    const bool full = (Co == 4 * CT) && (ep.u == nullptr || ep.Cu == 4 * CT);
+    const dim3 grid((unsigned)gx, (unsigned)B);
+    const int blob_floats = zt_mfma_blob(az, Nt, mt, Co, ep.u ? ep.Cu : 0, qf);
+    if (tables == nullptr || (size_t)G * blob_floats * 4 > kZtTablesBytes) return hipErrorInvalidValue;
+    hipLaunchKernelGGL(zt_tables_kernel, dim3(G), dim3(256), 0, s, tables, twt, twz, ep.u ? ep.W : nullptr,
+                       ep.w_so, ep.w_si, Co, ep.u ? ep.Cu : 0, 4 * CT, mt, Nt, az.L, az.P, qf, blob_floats);
+#define FNO_ZTM(NTV, MZV, CTV, FULLV)                                                              \
+  hipLaunchKernelGGL((zt_inv_mfma_kernel<NTV, MZV, CTV, FULLV>), grid, dim3(thr), lds, s, a, out,  \
+                     twt, twz, Co, NxNy, az.N, az.L, az.npos, mt, ilog2(qf), ilog2(G), inv_mt,        \
+                     zt_mfma_region(az, mt, Co, qf), inv_ch4, tables, blob_floats, e)
+#define FNO_ZTM_F(NTV, MZV, CTV)                         \
+  do {                                                   \
+    if (full) FNO_ZTM(NTV, MZV, CTV, true);              \
+    else FNO_ZTM(NTV, MZV, CTV, false);                  \
+  } while (0)
 #define FNO_ZTM_CT(NTV, MZV)                            \
   do {                                                  \
-    if (CT == 2) FNO_ZTM(NTV, MZV, 2);                  \
-    else if (CT == 5) FNO_ZTM(NTV, MZV, 5);             \
-    else FNO_ZTM(NTV, MZV, 8);                          \
+    if (CT == 2) FNO_ZTM_F(NTV, MZV, 2);                \
+    else if (CT == 5) FNO_ZTM_F(NTV, MZV, 5);           \
+    else FNO_ZTM_F(NTV, MZV, 8);                        \
   } while (0)
 #define FNO_ZTM_M(NTV)                                  \
   do {                                                  \
@@ -1044,6 +1194,7 @@ hipError_t launch_zt_inv(const float2* a, float* out, const float2* twt, const f
     if (Nt == 16) FNO_ZTM_M(16); else FNO_ZTM_M(32);
 #undef FNO_ZTM_M
 #undef FNO_ZTM_CT
+#undef FNO_ZTM_F
 #undef FNO_ZTM
     return hipGetLastError();
   }

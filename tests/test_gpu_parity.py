@@ -76,10 +76,10 @@ SMALL = [
     (1, 2, 2, (8, 4, 8, 8), (1, 1, 1, 1), 0),          # a single t mode
     (1, 1, 1, (1, 1, 1, 1), (0, 0, 0, 1), 1),          # one-point grid
     (1, 3, 2, (10, 3, 20, 5), (2, 1, 4, 2), 1),        # mixed radix z (20 = 5*4)
-    (1, 3, 3, (2, 3, 16, 16), (1, 1, 4, 5), 0),        # matrix-core inverse kernel, 6 columns, padded channels
+    (1, 3, 3, (2, 3, 32, 16), (1, 1, 4, 5), 0),        # matrix-core inverse kernel, 6 columns, padded channels
     (2, 2, 3, (3, 2, 32, 16), (1, 1, 6, 9), 0),        # same, two residue classes per block, Cin != Cout
     (1, 20, 20, (2, 2, 32, 32), (1, 1, 8, 9), 0),      # same, width 20, Nt = 32
-    (1, 24, 24, (2, 2, 16, 16), (1, 1, 4, 4), 0),      # same, width 24 (eight channel tiles)
+    (1, 24, 24, (2, 2, 32, 16), (1, 1, 4, 4), 0),      # same, width 24 (eight channel tiles)
 ]
 
 
