@@ -14,9 +14,6 @@
 
 namespace fno {
 
-unsigned long long* g_dbg = nullptr;
-extern "C" void fno_debug_set(unsigned long long* p) { g_dbg = p; }
-
 namespace {
 
 constexpr int kThreads = 256;
@@ -425,7 +422,6 @@ __global__ __launch_bounds__(kThreads) void mix_bwd_kernel(
 // ------------------------------------------------------------------------------------------
 struct EpiArgs {
   const float* u; int Cu; const float* W; int w_so, w_si; const float* bias; float* zsave; int act;
-  unsigned long long* dbg;
 };
 
 template <int MZ, int CO>
@@ -570,12 +566,11 @@ __global__ void zt_tables_kernel(float* __restrict__ blob, const float2* __restr
   }
 }
 
-#define FNO_TS(n) do { if (ep.dbg != nullptr && (tid & 63) == 0) { unsigned long long t_ = clock64(); if (tid == 0) { atomicAdd(ep.dbg + (n), t_ - tprev); } tprev = t_; } } while (0)
-// Launch: grid (8 * G * ceil(NxNy / 8), B), 256 threads.  Q and G are powers of two (shifts
+// Launch: grid (8 * G * ceil(NxNy / 8), B), 64 NW threads (a tile of NW * 128 / NT rows).  Q and G are powers of two (shifts
 // instead of divisions); inv_mt = ceil(2^16 / mt) turns the division by mt into a multiply.
 // FULL means Co == 4 CT and (no linear term or Cu == 4 CT): channel guards vanish at compile time.
-template <int NT, int MZ, int CT, bool FULL>
-__global__ __launch_bounds__(256, (MZ >= 32 || CT >= 8) ? 2 : 3) void zt_inv_mfma_kernel(
+template <int NT, int MZ, int CT, bool FULL, int NW, int ZI>
+__global__ __launch_bounds__(64 * NW, NW == 8 ? 4 : ((MZ >= 32 || CT >= 8) ? 2 : 3)) void zt_inv_mfma_kernel(
     const float2* __restrict__ a, float* __restrict__ out, const float2* __restrict__ twt,
     const float2* __restrict__ twz, int Co_rt, int NxNy, int Nz, int Lz, int nposz, int mt,
     int qshift, int gshift, int inv_mt, int region_floats, unsigned inv_ch4, const float* __restrict__ blob, int blob_floats, EpiArgs ep) {
@@ -584,12 +579,12 @@ __global__ __launch_bounds__(256, (MZ >= 32 || CT >= 8) ? 2 : 3) void zt_inv_mfm
   constexpr int CI = CP;                     // bound of the input-channel loop
   constexpr int QPR = NT / 4;                // quads per row
   constexpr int RPW = 32 / QPR;              // rows per wave: 16 MFMA blocks x 2 slots = 32 quads
-  constexpr int Rz = 4 * RPW;                // rows per tile (4 waves)
+  constexpr int Rz = NW * RPW;               // rows per tile (NW waves)
   const int Co = FULL ? CP : Co_rt;
   const int Cu = FULL ? CI : ep.Cu;
   const int Q = 1 << qshift;
   const int Pz = Nz / MZ;
-  constexpr int nthr = 256;
+  constexpr int nthr = 64 * NW;
   // LDS: the column's spectrum tile A [Co][Lz][mt] (complex), staged by LDS-direct loads; once
   // every z-stage item has read it, the same memory holds V [CP][Rz][mt].  Then the tables.
   float2* A = reinterpret_cast<float2*>(smem);
@@ -604,7 +599,6 @@ __global__ __launch_bounds__(256, (MZ >= 32 || CT >= 8) ? 2 : 3) void zt_inv_mfm
   const int xy = ((slot_id >> gshift) << 3) + xcd;
   const int g = slot_id & ((1 << gshift) - 1);
   if (xy >= NxNy) return;
-  unsigned long long tprev = clock64();
   const long long b = blockIdx.y;
   const int lane = tid & 63, wave = tid >> 6;
   const int j4 = lane & 3;                    // t within the quad (A side) / channel within the tile (B, D side)
@@ -626,7 +620,7 @@ __global__ __launch_bounds__(256, (MZ >= 32 || CT >= 8) ? 2 : 3) void zt_inv_mfm
   // tables: one contiguous blob per residue group, prepared by zt_tables_kernel in the LDS layout
   {
     const float* bsrc = blob + (long long)g * blob_floats;
-    for (int c0 = wave * 256; c0 < blob_floats; c0 += 1024)
+    for (int c0 = wave * 256; c0 < blob_floats; c0 += 256 * NW)
       __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(bsrc + c0 + 4 * lane),
                                        (__attribute__((address_space(3))) void*)(CS + c0), 16, 0, 0);
   }
@@ -638,7 +632,7 @@ __global__ __launch_bounds__(256, (MZ >= 32 || CT >= 8) ? 2 : 3) void zt_inv_mfm
     const int nf4 = Co * per_ch4;
     const float2* abase = a + ((b * Co) * NxNy + xy) * (long long)(Lz * mt);
     const long long astride = (long long)NxNy * Lz * mt; // float2 between channels
-    for (int c0 = wave * 64; c0 < nf4; c0 += 256) {
+    for (int c0 = wave * 64; c0 < nf4; c0 += nthr) {
       int f = c0 + lane;
       f = f < nf4 ? f : nf4 - 1;
       const int o = (int)__umulhi((unsigned)f, inv_ch4);
@@ -672,18 +666,16 @@ __global__ __launch_bounds__(256, (MZ >= 32 || CT >= 8) ? 2 : 3) void zt_inv_mfm
   } else {
     __builtin_amdgcn_s_waitcnt(0x0F70);
   }
-  FNO_TS(0);
   __syncthreads();
-  FNO_TS(1);
 
   // z stage: item (o, kt, q) collects the kept z-frequencies of one (channel, kt) column with
   // their twiddles into MZ bins; an inverse FFT over n1 gives the rows z = Pz n1 + n2.  At most
   // kZItems items per thread; their results wait in registers until every item has read A.
-  constexpr int kZItems = 2;
+  constexpr int kZItems = ZI;
   float2 gres[kZItems][MZ];
 #pragma unroll
   for (int it = 0; it < kZItems; ++it) {
-    const int item = tid + it * 256;
+    const int item = tid + it * nthr;
     if (item < nitems) {
       const int q = item & (Q - 1);
       const int r = item >> qshift;
@@ -703,11 +695,10 @@ __global__ __launch_bounds__(256, (MZ >= 32 || CT >= 8) ? 2 : 3) void zt_inv_mfm
       fft_reg<MZ, +1>(gres[it]);
     }
   }
-  FNO_TS(2);
   __syncthreads();
 #pragma unroll
   for (int it = 0; it < kZItems; ++it) {
-    const int item = tid + it * 256;
+    const int item = tid + it * nthr;
     if (item < nitems) {
       const int q = item & (Q - 1);
       const int r = item >> qshift;
@@ -724,7 +715,6 @@ __global__ __launch_bounds__(256, (MZ >= 32 || CT >= 8) ? 2 : 3) void zt_inv_mfm
     for (int idx = tid; idx < (CP - Co) * Rz * mt; idx += nthr) V[Co * Rz * mt + idx] = make_float2(0.f, 0.f);
   }
   __syncthreads();
-  FNO_TS(3);
 
   v4f acc[CT][2];
 #pragma unroll
@@ -756,7 +746,6 @@ __global__ __launch_bounds__(256, (MZ >= 32 || CT >= 8) ? 2 : 3) void zt_inv_mfm
       }
     }
   }
-  FNO_TS(4);
   const float* cs_lane = CS + 4 * quad + j4;
   const float2* v0 = V + (j4 * Rz + rowt[0]) * mt;
   const float2* v1 = V + (j4 * Rz + rowt[1]) * mt;
@@ -777,8 +766,6 @@ __global__ __launch_bounds__(256, (MZ >= 32 || CT >= 8) ? 2 : 3) void zt_inv_mfm
       acc[T][1] = __builtin_amdgcn_mfma_f32_4x4x1f32(sn, vb[T].y, acc[T][1], 0, 0, 0);
     }
   }
-
-  FNO_TS(5);
   // lane 4b+j now holds channel 4T+j at the four t of each of its two quads
   float* op = out + (b * Co + j4) * Npts;
   if (ep.zsave != nullptr) {
@@ -815,8 +802,6 @@ __global__ __launch_bounds__(256, (MZ >= 32 || CT >= 8) ? 2 : 3) void zt_inv_mfm
       }
     }
   }
-  FNO_TS(6);
-  if (ep.dbg != nullptr && tid == 0) atomicAdd(ep.dbg + 7, 1ull);
 }
 
 // ------------------------------------------------------------------------------------------
@@ -989,15 +974,17 @@ bool zt_inv_fits(AxisPlan az, int Nt, int mt, int Co) {
   return Co <= kMaxCo && zt_inv_lds(az, Nt, mt, Co) <= (size_t)(64 * 1024);
 }
 bool axis_fits(AxisPlan ax) { return (size_t)ax.N * 8 <= (size_t)kLdsBudget; }
-int mfma_q(AxisPlan az, int Nt);
+int mfma_q_nw(AxisPlan az, int Nt, int nw);
+int mfma_nw(AxisPlan az, int Nt, int mt, int Co, int Cu);
 size_t zt_mfma_lds(AxisPlan az, int Nt, int mt, int Co, int Cu, int q);
-bool zt_mfma_fits(AxisPlan az, int Nt, int mt, int Co, int Cu) {
-  const int q = mfma_q(az, Nt);
+bool mfma_cfg_ok(AxisPlan az, int Nt, int mt, int Co, int Cu, int nw, size_t lds_cap) {
+  const int q = mfma_q_nw(az, Nt, nw);
   const int CT = (Co + 3) / 4 <= 2 ? 2 : ((Co + 3) / 4 <= 5 ? 5 : 8);
   // the tile is staged in 16-byte pieces (L * mt even) and a thread owns at most two z-stage items
-  return q > 0 && q * az.L <= 512 && (az.L * mt) % 2 == 0 && Co * mt * q <= 512 && Co <= kMaxCo &&
-         Cu <= 4 * CT && zt_mfma_lds(az, Nt, mt, Co, Cu, q) <= (size_t)(80 * 1024);
+  return q > 0 && (az.L * mt) % 2 == 0 && Co * mt * q <= 2 * 64 * nw && Co <= kMaxCo && Cu <= 4 * CT &&
+         (nw == 4 || CT <= 5) && zt_mfma_lds(az, Nt, mt, Co, Cu, q) <= lds_cap;
 }
+bool zt_mfma_fits(AxisPlan az, int Nt, int mt, int Co, int Cu) { return mfma_nw(az, Nt, mt, Co, Cu) > 0; }
 
 hipError_t launch_axis_table(float2* tw, AxisPlan ax, hipStream_t s) {
   const int n = ax.L * ax.P;
@@ -1112,16 +1099,28 @@ hipError_t launch_mix_bwd(const float2* xh, const float2* R, const float2* gh, f
 
 // Tile of the matrix-core kernel: Q residue classes whose Rz = Q*M rows times Nt points make
 // 128..512 points (64..256 threads, two points each) and whose Q adjacent rows span at least 128 bytes.
-int mfma_q(AxisPlan az, int Nt) {
+// Rows per tile for NW waves: each wave covers 128 points.  Returns Q = rows / M, or 0.
+int mfma_q_nw(AxisPlan az, int Nt, int nw) {
   if (Nt != 16 && Nt != 32) return 0;
   if (az.M != 8 && az.M != 16 && az.M != 32) return 0;
   if (az.P & (az.P - 1)) return 0;                 // residue-class count must be a power of two
-  const int rz = 4 * (32 / (Nt / 4));              // rows per tile: 16 for Nt = 32, 32 for Nt = 16
+  const int rz = nw * (128 / Nt);
   if (rz % az.M) return 0;
   const int q = rz / az.M;
   if (q > az.P) return 0;
   return q;
 }
+
+bool mfma_cfg_ok(AxisPlan az, int Nt, int mt, int Co, int Cu, int nw, size_t lds_cap);
+
+// Eight waves (two blocks per CU) when the tile then still fits half a CU's LDS, else four.
+int mfma_nw(AxisPlan az, int Nt, int mt, int Co, int Cu) {
+  if (mfma_cfg_ok(az, Nt, mt, Co, Cu, 8, 78 * 1024)) return 8;
+  if (mfma_cfg_ok(az, Nt, mt, Co, Cu, 4, 80 * 1024)) return 4;
+  return 0;
+}
+
+int mfma_q(AxisPlan az, int Nt) { return mfma_q_nw(az, Nt, 4); }
 
 int ilog2(int v) { int l = 0; while ((1 << l) < v) ++l; return l; }
 
@@ -1148,36 +1147,48 @@ hipError_t launch_zt_inv(const float2* a, float* out, const float2* twt, const f
   const int64_t ncols = (int64_t)B * Nx * Ny;
   if (ncols <= 0) return hipSuccess;
   if (Co > kMaxCo) return hipErrorInvalidValue;
-  EpiArgs e{ep.u, ep.Cu, ep.W, ep.w_so, ep.w_si, ep.bias, ep.zsave, ep.act, g_dbg};
+  EpiArgs e{ep.u, ep.Cu, ep.W, ep.w_so, ep.w_si, ep.bias, ep.zsave, ep.act};
   const int NxNy = Nx * Ny;
   const int CT = (Co + 3) / 4 <= 2 ? 2 : ((Co + 3) / 4 <= 5 ? 5 : 8);
-  const int qf = mfma_q(az, Nt);
+  const int nw = mfma_nw(az, Nt, mt, Co, ep.u ? ep.Cu : 0);
+  const int qf = nw > 0 ? mfma_q_nw(az, Nt, nw) : 0;
   const bool aligned = ((reinterpret_cast<uintptr_t>(out) | reinterpret_cast<uintptr_t>(ep.u) |
-                         reinterpret_cast<uintptr_t>(ep.zsave)) & 15) == 0;
-  if (qf > 0 && aligned && zt_mfma_fits(az, Nt, mt, Co, ep.u ? ep.Cu : 0) &&
-      ((reinterpret_cast<uintptr_t>(a) | reinterpret_cast<uintptr_t>(tables)) & 15) == 0) {
+                         reinterpret_cast<uintptr_t>(ep.zsave) | reinterpret_cast<uintptr_t>(a) |
+                         reinterpret_cast<uintptr_t>(tables)) & 15) == 0;
+  if (qf > 0 && aligned) {
     const int G = az.P / qf;
     const int64_t gx = (int64_t)((NxNy + 7) / 8) * 8 * G;
     if (gx > 0x7fffffffLL || B > 65535 || Co * mt > 7000) return hipErrorInvalidValue;
-    const int thr = 256;
+    const int thr = 64 * nw;
     const size_t lds = zt_mfma_lds(az, Nt, mt, Co, ep.u ? ep.Cu : 0, qf);
     const int inv_mt = (65536 + mt - 1) / mt;
     const unsigned per_ch4 = (unsigned)(az.L * mt) / 2;
     const unsigned inv_ch4 = (unsigned)((0x100000000ULL + per_ch4 - 1) / per_ch4);
     const bool full = (Co == 4 * CT) && (ep.u == nullptr || ep.Cu == 4 * CT);
+    const bool one_item = Co * mt * qf <= thr;
     const dim3 grid((unsigned)gx, (unsigned)B);
     const int blob_floats = zt_mfma_blob(az, Nt, mt, Co, ep.u ? ep.Cu : 0, qf);
     if (tables == nullptr || (size_t)G * blob_floats * 4 > kZtTablesBytes) return hipErrorInvalidValue;
     hipLaunchKernelGGL(zt_tables_kernel, dim3(G), dim3(256), 0, s, tables, twt, twz, ep.u ? ep.W : nullptr,
                        ep.w_so, ep.w_si, Co, ep.u ? ep.Cu : 0, 4 * CT, mt, Nt, az.L, az.P, qf, blob_floats);
-#define FNO_ZTM(NTV, MZV, CTV, FULLV)                                                              \
-  hipLaunchKernelGGL((zt_inv_mfma_kernel<NTV, MZV, CTV, FULLV>), grid, dim3(thr), lds, s, a, out,  \
-                     twt, twz, Co, NxNy, az.N, az.L, az.npos, mt, ilog2(qf), ilog2(G), inv_mt,        \
-                     zt_mfma_region(az, mt, Co, qf), inv_ch4, tables, blob_floats, e)
+#define FNO_ZTM(NTV, MZV, CTV, FULLV, NWV, ZIV)                                                     \
+  hipLaunchKernelGGL((zt_inv_mfma_kernel<NTV, MZV, CTV, FULLV, NWV, ZIV>), grid, dim3(thr), lds, s, \
+                     a, out, twt, twz, Co, NxNy, az.N, az.L, az.npos, mt, ilog2(qf), ilog2(G),      \
+                     inv_mt, zt_mfma_region(az, mt, Co, qf), inv_ch4, tables, blob_floats, e)
+#define FNO_ZTM_Z(NTV, MZV, CTV, FULLV, NWV)                 \
+  do {                                                       \
+    if (one_item) FNO_ZTM(NTV, MZV, CTV, FULLV, NWV, 1);     \
+    else FNO_ZTM(NTV, MZV, CTV, FULLV, NWV, 2);              \
+  } while (0)
+#define FNO_ZTM_W(NTV, MZV, CTV, FULLV)                                 \
+  do {                                                                  \
+    if (nw == 8) { if constexpr (CTV <= 5) FNO_ZTM_Z(NTV, MZV, CTV, FULLV, 8); } \
+    else FNO_ZTM_Z(NTV, MZV, CTV, FULLV, 4);                            \
+  } while (0)
 #define FNO_ZTM_F(NTV, MZV, CTV)                         \
   do {                                                   \
-    if (full) FNO_ZTM(NTV, MZV, CTV, true);              \
-    else FNO_ZTM(NTV, MZV, CTV, false);                  \
+    if (full) FNO_ZTM_W(NTV, MZV, CTV, true);            \
+    else FNO_ZTM_W(NTV, MZV, CTV, false);                \
   } while (0)
 #define FNO_ZTM_CT(NTV, MZV)                            \
   do {                                                  \
@@ -1195,6 +1206,8 @@ hipError_t launch_zt_inv(const float2* a, float* out, const float2* twt, const f
 #undef FNO_ZTM_M
 #undef FNO_ZTM_CT
 #undef FNO_ZTM_F
+#undef FNO_ZTM_W
+#undef FNO_ZTM_Z
 #undef FNO_ZTM
     return hipGetLastError();
   }
