@@ -179,52 +179,78 @@ __device__ __forceinline__ void rfft_bins(const float2 (&zc)[NT / 2], int mt, fl
   (rfft_bin<NT, Ks>(zc, mt, X), ...);
 }
 
-// Bins 0..mt-1 of the real-input transform of one row of NT floats (16-byte aligned, in LDS).
+// Bins 0..mt-1 of the real-input transform of one row of NT floats held as NT/4 float4 quads.
 template <int NT>
-__device__ __forceinline__ void rfft_row_bins(const float* __restrict__ srow, int mt, float2 (&X)[NT / 2 + 1]) {
+__device__ __forceinline__ void rfft_row_bins(const float4 (&quads)[NT / 4], int mt, float2 (&X)[NT / 2 + 1]) {
   constexpr int H = NT / 2;
   float2 zc[H];
 #pragma unroll
   for (int m4 = 0; m4 < NT / 4; ++m4) {
-    const float4 v = *reinterpret_cast<const float4*>(srow + 4 * m4);
-    zc[2 * m4] = make_float2(v.x, v.y);
-    zc[2 * m4 + 1] = make_float2(v.z, v.w);
+    zc[2 * m4] = make_float2(quads[m4].x, quads[m4].y);
+    zc[2 * m4 + 1] = make_float2(quads[m4].z, quads[m4].w);
   }
   fft_reg<H, -1>(zc);
   rfft_bins<NT>(zc, mt, X, std::make_integer_sequence<int, H + 1>{});
 }
 
-// One thread per z-row (blockDim.x >= ppb * Nz).  The t-stage results wait in registers over a
-// barrier so the complex tile T can reuse the LDS of the real tile S.
+// One thread per z-row (blockDim.x >= ppb * Nz).  The planes and the z twiddles go straight to
+// LDS (16 bytes per lane, 1 KiB per wave instruction, nothing staged in registers).  Inside a
+// row the quads are stored rotated by the row number so that the row-per-thread reads of the
+// t stage spread over all banks; a wave's load still covers whole 128-byte lines.  The t-stage
+// results wait in registers over a barrier so the complex tile T can reuse the LDS of S.
+// Pz is a power of two and inv_mt = ceil(2^16 / mt) (shifts and a multiply instead of divisions).
 template <int NT, int MZ>
 __global__ __launch_bounds__(kThreads) void tz_fwd_fast_kernel(
     const float* __restrict__ x, float2* __restrict__ out, const float2* __restrict__ twz,
-    long long planes, int Nz, int Lz, int nposz, int mt, int ppb, int region_floats) {
+    long long planes, int Nz, int Lz, int nposz, int mt, int ppb, int region_floats, int pzshift,
+    int inv_mt) {
   HIP_DYNAMIC_SHARED(float, smem)
-  const int Pz = Nz / MZ;
-  constexpr int sS = NT + 4;                   // row stride of S in floats (keeps float4 alignment)
+  constexpr int QPR = NT / 4;                  // quads per row
+  constexpr int ROT = 16 / QPR > 0 ? 16 / QPR : 1;   // rows that share a rotation
   constexpr int H = NT / 2;
+  const int Pz = 1 << pzshift;
   const int sT = Nz + 1;                       // row stride of T in float2
-  float* S = smem;                             // [ppb][Nz][sS]
+  float* S = smem;                             // [ppb * Nz] rows of QPR rotated quads
   float2* T = reinterpret_cast<float2*>(smem); // [ppb][mt][sT], same memory, later
   float2* TW = reinterpret_cast<float2*>(smem + region_floats);   // [Lz][Pz]
   const int tid = threadIdx.x;
   const int nthr = blockDim.x;
+  const int lane = tid & 63, wave = tid >> 6;
   const long long plane0 = (long long)blockIdx.x * ppb;
   const int np = (int)min((long long)ppb, planes - plane0);
-  const int plane_quads = Nz * (NT / 4);
 
-  const float4* src = reinterpret_cast<const float4*>(x + plane0 * Nz * NT);
-  for (int idx = tid; idx < np * plane_quads; idx += nthr) {
-    const int row = idx / (NT / 4), q4 = idx - row * (NT / 4);
-    *reinterpret_cast<float4*>(S + row * sS + 4 * q4) = src[idx];
+  {
+    const float4* src = reinterpret_cast<const float4*>(x + plane0 * Nz * NT);
+    const int tot4 = np * Nz * QPR;            // a multiple of 64 (checked on the host)
+    for (int c0 = wave * 64; c0 < tot4; c0 += nthr) {
+      const int p4 = c0 + lane;
+      const int zl = p4 / QPR, sl = p4 - zl * QPR;
+      const int q = (sl - zl / ROT) & (QPR - 1);
+      __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(src + zl * QPR + q),
+                                       (__attribute__((address_space(3))) void*)(S + 4 * c0), 16, 0, 0);
+    }
+    const float4* tsrc = reinterpret_cast<const float4*>(twz);
+    const int tw4 = (Lz << pzshift) >> 1;      // float4 pieces of the twiddle table (Lz * Pz even)
+    for (int c0 = wave * 64; c0 < tw4; c0 += nthr) {
+      int f = c0 + lane;
+      f = f < tw4 ? f : tw4 - 1;
+      __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(tsrc + f),
+                                       (__attribute__((address_space(3))) void*)(smem + region_floats + 4 * c0),
+                                       16, 0, 0);
+    }
   }
-  for (int idx = tid; idx < Lz * Pz; idx += nthr) TW[idx] = twz[idx];
+  __builtin_amdgcn_s_waitcnt(0x0F70);          // vmcnt(0)
   __syncthreads();
 
   const bool live = tid < np * Nz;
   float2 X[H + 1];
-  if (live) rfft_row_bins<NT>(S + tid * sS, mt, X);
+  if (live) {
+    float4 quads[QPR];
+#pragma unroll
+    for (int q = 0; q < QPR; ++q)
+      quads[q] = *reinterpret_cast<const float4*>(S + 4 * (tid * QPR + ((q + tid / ROT) & (QPR - 1))));
+    rfft_row_bins<NT>(quads, mt, X);
+  }
   __syncthreads();
   if (live) {
     const int p = tid / Nz, z = tid - p * Nz;
@@ -235,29 +261,31 @@ __global__ __launch_bounds__(kThreads) void tz_fwd_fast_kernel(
   __syncthreads();
 
   if constexpr (MZ > 1) {
-    for (int idx = tid; idx < np * mt * Pz; idx += nthr) {
-      const int n2 = idx % Pz, col = idx / Pz;
+    for (int idx = tid; idx < ((np * mt) << pzshift); idx += nthr) {
+      const int n2 = idx & (Pz - 1), col = idx >> pzshift;
       float2* base = T + col * sT + n2;
       float2 a[MZ];
 #pragma unroll
-      for (int n1 = 0; n1 < MZ; ++n1) a[n1] = base[Pz * n1];
+      for (int n1 = 0; n1 < MZ; ++n1) a[n1] = base[n1 << pzshift];
       fft_reg<MZ, -1>(a);
 #pragma unroll
-      for (int m = 0; m < MZ; ++m) base[Pz * m] = a[bitrev<MZ>(m)];
+      for (int m = 0; m < MZ; ++m) base[m << pzshift] = a[bitrev<MZ>(m)];
     }
     __syncthreads();
   }
 
-  for (int idx = tid; idx < np * Lz * mt; idx += nthr) {
-    const int kt = idx % mt;
-    const int jz = (idx / mt) % Lz;
-    const int p = idx / (mt * Lz);
-    const int mj = posmod(kfreq(jz, Lz, nposz), MZ);
-    const float2* base = T + (p * mt + kt) * sT + Pz * mj;
-    const float2* w = TW + jz * Pz;
-    float2 acc = make_float2(0.f, 0.f);
-    for (int n2 = 0; n2 < Pz; ++n2) acc = cfma(w[n2], base[n2], acc);
-    out[((plane0 + p) * Lz + jz) * mt + kt] = acc;
+  for (int p = 0; p < np; ++p) {
+    float2* dst = out + (plane0 + p) * (long long)(Lz * mt);
+    for (int idx = tid; idx < Lz * mt; idx += nthr) {
+      const int jz = (idx * inv_mt) >> 16;
+      const int kt = idx - jz * mt;
+      const int mj = posmod(kfreq(jz, Lz, nposz), MZ);
+      const float2* base = T + (p * mt + kt) * sT + (mj << pzshift);
+      const float2* w = TW + (jz << pzshift);
+      float2 acc = make_float2(0.f, 0.f);
+      for (int n2 = 0; n2 < Pz; ++n2) acc = cfma(w[n2], base[n2], acc);
+      dst[idx] = acc;
+    }
   }
 }
 
@@ -569,8 +597,8 @@ __global__ void zt_tables_kernel(float* __restrict__ blob, const float2* __restr
 // Launch: grid (8 * G * ceil(NxNy / 8), B), 64 NW threads (a tile of NW * 128 / NT rows).  Q and G are powers of two (shifts
 // instead of divisions); inv_mt = ceil(2^16 / mt) turns the division by mt into a multiply.
 // FULL means Co == 4 CT and (no linear term or Cu == 4 CT): channel guards vanish at compile time.
-template <int NT, int MZ, int CT, bool FULL, int NW, int ZI>
-__global__ __launch_bounds__(64 * NW, NW == 8 ? 4 : ((MZ >= 32 || CT >= 8) ? 2 : 3)) void zt_inv_mfma_kernel(
+template <int NT, int MZ, int CT, bool FULL, int NW>
+__global__ __launch_bounds__(64 * NW, NW == 8 ? 4 : (CT >= 8 ? 2 : 3)) void zt_inv_mfma_kernel(
     const float2* __restrict__ a, float* __restrict__ out, const float2* __restrict__ twt,
     const float2* __restrict__ twz, int Co_rt, int NxNy, int Nz, int Lz, int nposz, int mt,
     int qshift, int gshift, int inv_mt, int region_floats, unsigned inv_ch4, const float* __restrict__ blob, int blob_floats, EpiArgs ep) {
@@ -671,7 +699,7 @@ __global__ __launch_bounds__(64 * NW, NW == 8 ? 4 : ((MZ >= 32 || CT >= 8) ? 2 :
   // z stage: item (o, kt, q) collects the kept z-frequencies of one (channel, kt) column with
   // their twiddles into MZ bins; an inverse FFT over n1 gives the rows z = Pz n1 + n2.  At most
   // kZItems items per thread; their results wait in registers until every item has read A.
-  constexpr int kZItems = ZI;
+  constexpr int kZItems = NW == 8 ? 1 : 2;      // z-stage items per thread (checked on the host)
   float2 gres[kZItems][MZ];
 #pragma unroll
   for (int it = 0; it < kZItems; ++it) {
@@ -981,7 +1009,7 @@ bool mfma_cfg_ok(AxisPlan az, int Nt, int mt, int Co, int Cu, int nw, size_t lds
   const int q = mfma_q_nw(az, Nt, nw);
   const int CT = (Co + 3) / 4 <= 2 ? 2 : ((Co + 3) / 4 <= 5 ? 5 : 8);
   // the tile is staged in 16-byte pieces (L * mt even) and a thread owns at most two z-stage items
-  return q > 0 && (az.L * mt) % 2 == 0 && Co * mt * q <= 2 * 64 * nw && Co <= kMaxCo && Cu <= 4 * CT &&
+  return q > 0 && (az.L * mt) % 2 == 0 && Co * mt * q <= (nw == 8 ? 512 : 512) && Co <= kMaxCo && Cu <= 4 * CT &&
          (nw == 4 || CT <= 5) && zt_mfma_lds(az, Nt, mt, Co, Cu, q) <= lds_cap;
 }
 bool zt_mfma_fits(AxisPlan az, int Nt, int mt, int Co, int Cu) { return mfma_nw(az, Nt, mt, Co, Cu) > 0; }
@@ -999,22 +1027,26 @@ hipError_t launch_t_table(float2* twt, int Nt, int mt, hipStream_t s) {
   return hipGetLastError();
 }
 
+int ilog2(int v);
 int tz_fast_region(AxisPlan az, int Nt, int mt, int ppb) {
-  const int s_floats = ppb * az.N * (Nt + 4);
+  const int s_floats = ppb * az.N * Nt;
   const int t_floats = 2 * ppb * mt * (az.N + 1);
   const int r = s_floats > t_floats ? s_floats : t_floats;
-  return (r + 3) & ~3;
+  return (r + 255) & ~255;
 }
 
 size_t tz_fast_lds(AxisPlan az, int Nt, int mt, int ppb) {
-  return (size_t)tz_fast_region(az, Nt, mt, ppb) * 4 + (size_t)az.L * az.P * 8;
+  const size_t tw_floats = ((size_t)az.L * az.P * 2 + 255) & ~size_t(255);      // whole 1 KiB loads
+  return ((size_t)tz_fast_region(az, Nt, mt, ppb) + tw_floats) * 4;
 }
 
 hipError_t launch_tz_fwd(const float* x, float2* out, const float2* twt, const float2* twz,
                          int64_t planes, AxisPlan az, int Nt, int mt, hipStream_t s) {
   if (planes <= 0) return hipSuccess;
-  const bool fast = (Nt == 16 || Nt == 32 || Nt == 64) && (az.M == 8 || az.M == 16 || az.M == 32) &&
-                    az.N <= kThreads && (reinterpret_cast<uintptr_t>(x) & 15) == 0 &&
+  const bool fast = (Nt == 16 || Nt == 32 || Nt == 64) && (az.M == 8 || az.M == 16) &&
+                    (az.P & (az.P - 1)) == 0 && (az.N * Nt) % 256 == 0 && (az.L * az.P) % 2 == 0 &&
+                    az.L * mt < 7000 && az.N <= kThreads &&
+                    ((reinterpret_cast<uintptr_t>(x) | reinterpret_cast<uintptr_t>(twz)) & 15) == 0 &&
                     tz_fast_lds(az, Nt, mt, 1) <= (size_t)kLdsBudget;
   if (fast) {
     int ppb = 1;
@@ -1024,14 +1056,15 @@ hipError_t launch_tz_fwd(const float* x, float2* out, const float2* twt, const f
     const int region = tz_fast_region(az, Nt, mt, ppb);
     const int64_t nblk = (planes + ppb - 1) / ppb;
     if (nblk > 0x7fffffffLL) return hipErrorInvalidValue;
+    const int inv_mt = (65536 + mt - 1) / mt;
 #define FNO_TZF(NTV, MZV)                                                                     \
   hipLaunchKernelGGL((tz_fwd_fast_kernel<NTV, MZV>), dim3((unsigned)nblk), dim3(thr), lds, s, \
-                     x, out, twz, (long long)planes, az.N, az.L, az.npos, mt, ppb, region)
+                     x, out, twz, (long long)planes, az.N, az.L, az.npos, mt, ppb, region,    \
+                     ilog2(az.P), inv_mt)
 #define FNO_TZF_M(NTV)                     \
   do {                                     \
     if (az.M == 8) FNO_TZF(NTV, 8);        \
-    else if (az.M == 16) FNO_TZF(NTV, 16); \
-    else FNO_TZF(NTV, 32);                 \
+    else FNO_TZF(NTV, 16);                 \
   } while (0)
     if (Nt == 16) FNO_TZF_M(16); else if (Nt == 32) FNO_TZF_M(32); else FNO_TZF_M(64);
 #undef FNO_TZF_M
@@ -1102,7 +1135,7 @@ hipError_t launch_mix_bwd(const float2* xh, const float2* R, const float2* gh, f
 // Rows per tile for NW waves: each wave covers 128 points.  Returns Q = rows / M, or 0.
 int mfma_q_nw(AxisPlan az, int Nt, int nw) {
   if (Nt != 16 && Nt != 32) return 0;
-  if (az.M != 8 && az.M != 16 && az.M != 32) return 0;
+  if (az.M != 8 && az.M != 16) return 0;
   if (az.P & (az.P - 1)) return 0;                 // residue-class count must be a power of two
   const int rz = nw * (128 / Nt);
   if (rz % az.M) return 0;
@@ -1165,49 +1198,37 @@ hipError_t launch_zt_inv(const float2* a, float* out, const float2* twt, const f
     const unsigned per_ch4 = (unsigned)(az.L * mt) / 2;
     const unsigned inv_ch4 = (unsigned)((0x100000000ULL + per_ch4 - 1) / per_ch4);
     const bool full = (Co == 4 * CT) && (ep.u == nullptr || ep.Cu == 4 * CT);
-    const bool one_item = Co * mt * qf <= thr;
     const dim3 grid((unsigned)gx, (unsigned)B);
     const int blob_floats = zt_mfma_blob(az, Nt, mt, Co, ep.u ? ep.Cu : 0, qf);
     if (tables == nullptr || (size_t)G * blob_floats * 4 > kZtTablesBytes) return hipErrorInvalidValue;
     hipLaunchKernelGGL(zt_tables_kernel, dim3(G), dim3(256), 0, s, tables, twt, twz, ep.u ? ep.W : nullptr,
                        ep.w_so, ep.w_si, Co, ep.u ? ep.Cu : 0, 4 * CT, mt, Nt, az.L, az.P, qf, blob_floats);
-#define FNO_ZTM(NTV, MZV, CTV, FULLV, NWV, ZIV)                                                     \
-  hipLaunchKernelGGL((zt_inv_mfma_kernel<NTV, MZV, CTV, FULLV, NWV, ZIV>), grid, dim3(thr), lds, s, \
-                     a, out, twt, twz, Co, NxNy, az.N, az.L, az.npos, mt, ilog2(qf), ilog2(G),      \
-                     inv_mt, zt_mfma_region(az, mt, Co, qf), inv_ch4, tables, blob_floats, e)
-#define FNO_ZTM_Z(NTV, MZV, CTV, FULLV, NWV)                 \
-  do {                                                       \
-    if (one_item) FNO_ZTM(NTV, MZV, CTV, FULLV, NWV, 1);     \
-    else FNO_ZTM(NTV, MZV, CTV, FULLV, NWV, 2);              \
-  } while (0)
-#define FNO_ZTM_W(NTV, MZV, CTV, FULLV)                                 \
-  do {                                                                  \
-    if (nw == 8) { if constexpr (CTV <= 5) FNO_ZTM_Z(NTV, MZV, CTV, FULLV, 8); } \
-    else FNO_ZTM_Z(NTV, MZV, CTV, FULLV, 4);                            \
-  } while (0)
-#define FNO_ZTM_F(NTV, MZV, CTV)                         \
-  do {                                                   \
-    if (full) FNO_ZTM_W(NTV, MZV, CTV, true);            \
-    else FNO_ZTM_W(NTV, MZV, CTV, false);                \
+#define FNO_ZTM(NTV, MZV, CTV, FULLV, NWV)                                                          \
+  hipLaunchKernelGGL((zt_inv_mfma_kernel<NTV, MZV, CTV, FULLV, NWV>), grid, dim3(thr), lds, s, a,   \
+                     out, twt, twz, Co, NxNy, az.N, az.L, az.npos, mt, ilog2(qf), ilog2(G), inv_mt, \
+                     zt_mfma_region(az, mt, Co, qf), inv_ch4, tables, blob_floats, e)
+#define FNO_ZTM_F(NTV, MZV, CTV)                                  \
+  do {                                                            \
+    if (nw == 8 && full) FNO_ZTM(NTV, MZV, CTV, true, 8);         \
+    else if (nw == 8) FNO_ZTM(NTV, MZV, CTV, false, 8);           \
+    else if (full) FNO_ZTM(NTV, MZV, CTV, true, 4);               \
+    else FNO_ZTM(NTV, MZV, CTV, false, 4);                        \
   } while (0)
 #define FNO_ZTM_CT(NTV, MZV)                            \
   do {                                                  \
     if (CT == 2) FNO_ZTM_F(NTV, MZV, 2);                \
     else if (CT == 5) FNO_ZTM_F(NTV, MZV, 5);           \
-    else FNO_ZTM_F(NTV, MZV, 8);                        \
+    else FNO_ZTM(NTV, MZV, 8, false, 4);                \
   } while (0)
 #define FNO_ZTM_M(NTV)                                  \
   do {                                                  \
     if (az.M == 8) FNO_ZTM_CT(NTV, 8);                  \
-    else if (az.M == 16) FNO_ZTM_CT(NTV, 16);           \
-    else FNO_ZTM_CT(NTV, 32);                           \
+    else FNO_ZTM_CT(NTV, 16);                           \
   } while (0)
     if (Nt == 16) FNO_ZTM_M(16); else FNO_ZTM_M(32);
 #undef FNO_ZTM_M
 #undef FNO_ZTM_CT
 #undef FNO_ZTM_F
-#undef FNO_ZTM_W
-#undef FNO_ZTM_Z
 #undef FNO_ZTM
     return hipGetLastError();
   }
