@@ -31,13 +31,13 @@ def parse():
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="only run plain device copies of 4 GiB (reference reading for rocprofv3 --pmc "
                          "FETCH_SIZE / WRITE_SIZE), then exit")
-    ap.add_argument("--traffic-file", default=os.path.join(ROOT, "profiles", "traffic.json"),
+    ap.add_argument("--traffic-file", default=os.path.join(ROOT, "profiles", "hbm_traffic.json.txt"),
                     help="measured HBM bytes per launch of the dominant kernel (from rocprofv3 --pmc)")
     return ap.parse_args()
 
 
 def cpu_baseline(cfg):
-    """The oracle as it stands on a bounded sample: a width-1 block on a 64-wide x-slice."""
+    """The oracle as it stands on a bounded sample: a width-1 block on one channel slab of the grid."""
     import numpy as np
     from oracle import fno_oracle as O
     from paper_2204_01205_amd import synth
@@ -46,12 +46,7 @@ def cpu_baseline(cfg):
         threads = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
     except Exception:
         threads = len(os.sched_getaffinity(0))
-    nx, ny, nz, nt = cfg["grid"]
-    mx = cfg["modes"][0]
-    sx = min(nx, max(64, 2 * mx))
-    while sx < 2 * mx:
-        sx *= 2
-    grid = (sx, ny, nz, nt)
+    grid = tuple(cfg["grid"])
     spec = O.LayerSpec(grid, tuple(cfg["modes"]), 0)
     counts = synth.retained_counts(cfg["modes"])
     x = synth.normal_field(0, synth.T_X, 1, 1, grid)
@@ -63,8 +58,8 @@ def cpu_baseline(cfg):
     dt = time.perf_counter() - t0
     pc = float(np.prod(grid))
     return {"value": pc / dt / 1e9, "unit": "Gpoint-channels/s", "cores": int(threads), "kind": "oracle",
-            "sample": f"float64 oracle block_fwd, width 1, grid {grid[0]}x{grid[1]}x{grid[2]}x{grid[3]} "
-                      f"(an x-slice of one channel slab), modes as the workload; {dt:.1f} s",
+            "sample": f"float64 oracle block_fwd, width 1 (one of the workload's channel slabs), grid "
+                      f"{grid[0]}x{grid[1]}x{grid[2]}x{grid[3]}, modes as the workload; {dt:.1f} s",
             "host_cores_visible": len(os.sched_getaffinity(0))}
 
 

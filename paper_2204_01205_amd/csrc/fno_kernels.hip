@@ -601,7 +601,7 @@ template <int NT, int MZ, int CT, bool FULL, int NW>
 __global__ __launch_bounds__(64 * NW, NW == 8 ? 4 : (CT >= 8 ? 2 : 3)) void zt_inv_mfma_kernel(
     const float2* __restrict__ a, float* __restrict__ out, const float2* __restrict__ twt,
     const float2* __restrict__ twz, int Co_rt, int NxNy, int Nz, int Lz, int nposz, int mt,
-    int qshift, int gshift, int inv_mt, int region_floats, unsigned inv_ch4, const float* __restrict__ blob, int blob_floats, EpiArgs ep) {
+    int qshift, int gshift, int inv_mt, int region_floats, int a_stride4, int v_stride, const float* __restrict__ blob, int blob_floats, EpiArgs ep) {
   HIP_DYNAMIC_SHARED(float, smem)
   constexpr int CP = 4 * CT;                 // channels padded to whole MFMA tiles
   constexpr int CI = CP;                     // bound of the input-channel loop
@@ -614,7 +614,8 @@ __global__ __launch_bounds__(64 * NW, NW == 8 ? 4 : (CT >= 8 ? 2 : 3)) void zt_i
   const int Pz = Nz / MZ;
   constexpr int nthr = 64 * NW;
   // LDS: the column's spectrum tile A [Co][Lz][mt] (complex), staged by LDS-direct loads; once
-  // every z-stage item has read it, the same memory holds V [CP][Rz][mt].  Then the tables.
+  // every z-stage item has read it, the same memory holds V [CP][Rz][mt].  Both with padded
+  // channel strides.  Then the tables.
   float2* A = reinterpret_cast<float2*>(smem);
   float2* V = reinterpret_cast<float2*>(smem);
   float* CS = smem + region_floats;                     // [2 mt][NT]: cos rows and -sin rows
@@ -653,24 +654,23 @@ __global__ __launch_bounds__(64 * NW, NW == 8 ? 4 : (CT >= 8 ? 2 : 3)) void zt_i
                                        (__attribute__((address_space(3))) void*)(CS + c0), 16, 0, 0);
   }
   asm volatile("" ::: "memory");    // keep the issue order: tables, tile, u (the wait below counts on it)
-  // the spectrum tile goes straight to LDS: 16 bytes per lane, 1 KiB per wave instruction;
-  // lanes past the end re-read the last piece into the padding of the region
+  // the spectrum tile goes straight to LDS, 16 bytes per lane, channel by channel: the channel
+  // stride in LDS (a_stride4 float4) is padded so that the z-stage reads, whose lanes differ in
+  // (channel, kt), spread over the banks
   {
     const int per_ch4 = (Lz * mt) >> 1;                  // float4 pieces per channel
-    const int nf4 = Co * per_ch4;
     const float2* abase = a + ((b * Co) * NxNy + xy) * (long long)(Lz * mt);
     const long long astride = (long long)NxNy * Lz * mt; // float2 between channels
-    for (int c0 = wave * 64; c0 < nf4; c0 += nthr) {
-      int f = c0 + lane;
-      f = f < nf4 ? f : nf4 - 1;
-      const int o = (int)__umulhi((unsigned)f, inv_ch4);
-      const int r = f - o * per_ch4;
-      const float2* gsrc = abase + o * astride + 2 * r;
-      __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)gsrc,
-                                       (__attribute__((address_space(3))) void*)(smem + 4 * c0), 16, 0, 0);
+    for (int o = wave; o < Co; o += NW) {
+      for (int c0 = 0; c0 < per_ch4; c0 += 64) {
+        const int f = c0 + lane;
+        if (f < per_ch4)
+          __builtin_amdgcn_global_load_lds(
+              (const __attribute__((address_space(1))) void*)(abase + o * astride + 2 * f),
+              (__attribute__((address_space(3))) void*)(smem + 4 * (o * a_stride4 + c0)), 16, 0, 0);
+      }
     }
   }
-
   asm volatile("" ::: "memory");
   // u loads last so they stay in flight during the z stage: lane 4b+i takes t = 4 quad + i
   float xv[CI][2];
@@ -709,7 +709,7 @@ __global__ __launch_bounds__(64 * NW, NW == 8 ? 4 : (CT >= 8 ? 2 : 3)) void zt_i
       const int r = item >> qshift;
       const int o = (r * inv_mt) >> 16;
       const int kt = r - o * mt;
-      const float2* asrc = A + o * (Lz * mt) + kt;
+      const float2* asrc = A + o * (2 * a_stride4) + kt;
       const float2* twq = TWQ + q * Lz;
 #pragma unroll
       for (int m = 0; m < MZ; ++m) {
@@ -732,7 +732,7 @@ __global__ __launch_bounds__(64 * NW, NW == 8 ? 4 : (CT >= 8 ? 2 : 3)) void zt_i
       const int r = item >> qshift;
       const int o = (r * inv_mt) >> 16;
       const int kt = r - o * mt;
-      float2* vdst = V + ((o * Rz) + q) * mt + kt;
+      float2* vdst = V + o * v_stride + q * mt + kt;
       const int vstep = mt << qshift;
 #pragma unroll
       for (int n1 = 0; n1 < MZ; ++n1) vdst[n1 * vstep] = gres[it][bitrev<MZ>(n1)];
@@ -740,7 +740,7 @@ __global__ __launch_bounds__(64 * NW, NW == 8 ? 4 : (CT >= 8 ? 2 : 3)) void zt_i
   }
   if (!FULL) {
     // channels of the padding tiles: finite values so the unused MFMA columns stay harmless
-    for (int idx = tid; idx < (CP - Co) * Rz * mt; idx += nthr) V[Co * Rz * mt + idx] = make_float2(0.f, 0.f);
+    for (int idx = tid; idx < (CP - Co) * v_stride; idx += nthr) V[Co * v_stride + idx] = make_float2(0.f, 0.f);
   }
   __syncthreads();
 
@@ -775,16 +775,16 @@ __global__ __launch_bounds__(64 * NW, NW == 8 ? 4 : (CT >= 8 ? 2 : 3)) void zt_i
     }
   }
   const float* cs_lane = CS + 4 * quad + j4;
-  const float2* v0 = V + (j4 * Rz + rowt[0]) * mt;
-  const float2* v1 = V + (j4 * Rz + rowt[1]) * mt;
+  const float2* v0 = V + j4 * v_stride + rowt[0] * mt;     // channel stride padded against bank conflicts
+  const float2* v1 = V + j4 * v_stride + rowt[1] * mt;
   for (int kt = 0; kt < mt; ++kt) {
     const float c = cs_lane[(2 * kt) * NT];
     const float sn = cs_lane[(2 * kt + 1) * NT];
     float2 va[CT], vb[CT];
 #pragma unroll
     for (int T = 0; T < CT; ++T) {
-      va[T] = v0[(4 * T * Rz) * mt + kt];
-      vb[T] = v1[(4 * T * Rz) * mt + kt];
+      va[T] = v0[4 * T * v_stride + kt];
+      vb[T] = v1[4 * T * v_stride + kt];
     }
 #pragma unroll
     for (int T = 0; T < CT; ++T) {
@@ -1157,12 +1157,31 @@ int mfma_q(AxisPlan az, int Nt) { return mfma_q_nw(az, Nt, 4); }
 
 int ilog2(int v) { int l = 0; while ((1 << l) < v) ++l; return l; }
 
-// floats of the region shared by the spectrum tile (rounded up to whole 1 KiB wave loads) and V
+// LDS channel stride of the spectrum tile in float4: padded so that consecutive channels start
+// 2 mt .. 64 - 2 mt floats apart modulo the 64 banks
+int zt_mfma_astride4(AxisPlan az, int mt) {
+  const int per_ch4 = (az.L * mt) / 2;
+  for (int pad = 0; pad < 16; ++pad) {
+    const int r = (4 * (per_ch4 + pad)) % 64;
+    if (r >= 2 * mt && r <= 64 - 2 * mt) return per_ch4 + pad;
+  }
+  return per_ch4 + 1;
+}
+
+// channel stride of V in float2: rows * mt padded to 2 modulo 32, so that the four channels an
+// MFMA block reads together fall into different banks
+int zt_mfma_vstride(AxisPlan az, int mt, int q) {
+  const int base = q * az.M * mt;
+  return base + ((2 - base) % 32 + 32) % 32;
+}
+
+// floats of the region shared by the spectrum tile and V
 int zt_mfma_region(AxisPlan az, int mt, int Co, int q) {
   const int CT = (Co + 3) / 4 <= 2 ? 2 : ((Co + 3) / 4 <= 5 ? 5 : 8);
-  const int a_floats = ((Co * az.L * mt * 2 + 255) / 256) * 256;
-  const int v_floats = 2 * 4 * CT * q * az.M * mt;
-  return a_floats > v_floats ? a_floats : v_floats;
+  const int a_floats = Co * zt_mfma_astride4(az, mt) * 4 + 256;   // the last wave load may run 63 lanes past
+  const int v_floats = 2 * 4 * CT * zt_mfma_vstride(az, mt, q);
+  const int r = a_floats > v_floats ? a_floats : v_floats;
+  return (r + 255) & ~255;
 }
 
 int zt_mfma_blob(AxisPlan az, int Nt, int mt, int Co, int Cu, int q) {
@@ -1195,8 +1214,6 @@ hipError_t launch_zt_inv(const float2* a, float* out, const float2* twt, const f
     const int thr = 64 * nw;
     const size_t lds = zt_mfma_lds(az, Nt, mt, Co, ep.u ? ep.Cu : 0, qf);
     const int inv_mt = (65536 + mt - 1) / mt;
-    const unsigned per_ch4 = (unsigned)(az.L * mt) / 2;
-    const unsigned inv_ch4 = (unsigned)((0x100000000ULL + per_ch4 - 1) / per_ch4);
     const bool full = (Co == 4 * CT) && (ep.u == nullptr || ep.Cu == 4 * CT);
     const dim3 grid((unsigned)gx, (unsigned)B);
     const int blob_floats = zt_mfma_blob(az, Nt, mt, Co, ep.u ? ep.Cu : 0, qf);
@@ -1206,7 +1223,8 @@ hipError_t launch_zt_inv(const float2* a, float* out, const float2* twt, const f
 #define FNO_ZTM(NTV, MZV, CTV, FULLV, NWV)                                                          \
   hipLaunchKernelGGL((zt_inv_mfma_kernel<NTV, MZV, CTV, FULLV, NWV>), grid, dim3(thr), lds, s, a,   \
                      out, twt, twz, Co, NxNy, az.N, az.L, az.npos, mt, ilog2(qf), ilog2(G), inv_mt, \
-                     zt_mfma_region(az, mt, Co, qf), inv_ch4, tables, blob_floats, e)
+                     zt_mfma_region(az, mt, Co, qf), zt_mfma_astride4(az, mt), zt_mfma_vstride(az, mt, qf),  \
+                     tables, blob_floats, e)
 #define FNO_ZTM_F(NTV, MZV, CTV)                                  \
   do {                                                            \
     if (nw == 8 && full) FNO_ZTM(NTV, MZV, CTV, true, 8);         \
