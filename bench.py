@@ -100,11 +100,29 @@ def main():
     W = torch.randn((width, width), device="cuda", generator=gen) / float(width) ** 0.5
     b = 0.1 * torch.randn((width,), device="cuda", generator=gen)
     out = torch.empty_like(x)
-    desc = B.make_desc(batch, width, width, grid, modes, 0, B.FNO_ACT_GELU)
-    ws = B.alloc_workspace(desc, B.FNO_OP_BLOCK_FWD)
+    train = cfg["op"] == "block_fwd_bwd"
+    if train:
+        # one training step of a block: forward keeping z and the spectrum, backward with the
+        # MSE gradient against a seeded target fused into its first sweep
+        desc = B.make_desc(batch, width, width, grid, modes, 0, B.FNO_ACT_GELU, B.FNO_FLAG_MSE_TARGET)
+        ws = B.alloc_workspace(desc, B.FNO_OP_BLOCK_BWD)
+        target = torch.randn(x.shape, device="cuda", generator=gen)
+        z = torch.empty_like(x)
+        xh = torch.empty((batch, width) + counts, dtype=torch.complex64, device="cuda")
+        gx = torch.empty_like(x)
+        gR = torch.empty_like(R)
+        gW = torch.empty_like(W)
+        gb = torch.empty_like(b)
 
-    def step():
-        B.fno_block_fwd(desc, x, R, W, b, out, None, None, ws)
+        def step():
+            B.fno_block_fwd(desc, x, R, W, b, out, z, xh, ws)
+            B.fno_block_bwd(desc, x, R, W, z, xh, target, gx, gR, gW, gb, ws)
+    else:
+        desc = B.make_desc(batch, width, width, grid, modes, 0, B.FNO_ACT_GELU)
+        ws = B.alloc_workspace(desc, B.FNO_OP_BLOCK_FWD)
+
+        def step():
+            B.fno_block_fwd(desc, x, R, W, b, out, None, None, ws)
 
     for _ in range(args.warmup):
         step()
@@ -123,13 +141,17 @@ def main():
     stage_ms = {}
     for name, ms in records:
         stage_ms.setdefault(name, []).append(ms)
-    stage_avg = {k: sum(v) / len(v) for k, v in stage_ms.items()}
+    # per step: a stage that runs several times in a step (forward chain of x and of gz) is summed
+    stage_avg = {k: sum(v) / args.steps for k, v in stage_ms.items()}
+    stage_launches = {k: len(v) / args.steps for k, v in stage_ms.items()}
     dominant = max(stage_avg, key=stage_avg.get)
     # algorithmic bytes per launch of each full-grid sweep: 4 B per point-channel per tensor touched
     alg_bytes = {"zt_inv": 8.0 * pc,      # reads x for W x, writes out (pruned spectrum not counted)
-                 "tz_fwd": 4.0 * pc}      # reads x
+                 "tz_fwd": 4.0 * pc,      # reads x
+                 "bwd_pointwise": 16.0 * pc}   # reads z, target, x; writes gz
     dom_bytes = alg_bytes.get(dominant, 0.0)
-    achieved = dom_bytes / (stage_avg[dominant] * 1e-3) / 1e9
+    dom_launch_ms = stage_avg[dominant] / stage_launches[dominant]
+    achieved = dom_bytes / (dom_launch_ms * 1e-3) / 1e9
     traffic = None
     if os.path.exists(args.traffic_file):
         try:
@@ -139,7 +161,7 @@ def main():
                 traffic = ent
         except Exception:
             traffic = None
-    whole_bytes = 12.0 * pc + 8.0 * width * width * nmodes
+    whole_bytes = (40.0 * pc + 24.0 * width * width * nmodes) if train else (12.0 * pc + 8.0 * width * width * nmodes)
     line = {
         "metric": "FNO spectral layer Gpoint-channels/s + achieved HBM GB/s on 1 MI355X",
         "value": pc / (ms_per_step * 1e-3) / 1e9,
@@ -147,7 +169,7 @@ def main():
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "f32", "data": "synthetic",
-        "config": {"workload": f"{args.config}: fno_block_fwd, batch {batch}, width {width}, grid "
+        "config": {"workload": f"{args.config}: {'fno_block_fwd + fno_block_bwd (MSE)' if train else 'fno_block_fwd'}, batch {batch}, width {width}, grid "
                                f"{grid[0]}x{grid[1]}x{grid[2]}x{grid[3]}, kept modes {counts[0]}x{counts[1]}x{counts[2]}x{counts[3]}",
                    "global_batch": batch, "parallelism": "single GPU"},
         "whole_path": {"algorithmic_GB": whole_bytes / 1e9,
@@ -155,7 +177,7 @@ def main():
                        "frac_of_hbm_peak": whole_bytes / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS},
         "roofline": {"kernel": dominant, "bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS,
                      "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS, "traffic": traffic,
-                     "avg_launch_ms": stage_avg[dominant], "algorithmic_bytes_per_launch": dom_bytes},
+                     "avg_launch_ms": dom_launch_ms, "algorithmic_bytes_per_launch": dom_bytes},
         "stage_ms": stage_avg,
     }
     if not args.no_cpu_baseline:

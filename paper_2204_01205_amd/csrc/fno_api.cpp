@@ -342,10 +342,11 @@ int fno_block_bwd(const fno_desc* desc, const float* x, const float* R, const fl
   double* part = at<double>(ws, p.off_part);
   const int mse = (desc->flags & FNO_FLAG_MSE_TARGET) ? 1 : 0;
   const double mse_scale = 2.0 / (double(p.B) * double(p.Co) * double(p.Npts));
-  FNO_STAGE(FNO_STAGE_BWD_POINTWISE, s, fno::launch_bwd_pointwise(z_saved, gout, x, gz, part, p.part_blocks, p.B, p.Ci, p.Co,
+  int nslots = 0;
+  FNO_STAGE(FNO_STAGE_BWD_POINTWISE, s, fno::launch_bwd_pointwise(z_saved, gout, x, gz, part, &nslots, p.B, p.Ci, p.Co,
                                     p.Npts, desc->activation, mse, mse_scale, s));
   if (gW != nullptr || gb != nullptr)
-    FNO_HIP(fno::launch_reduce_partials(part, p.part_blocks, p.Co, p.Ci, gW, gb, s));
+    FNO_HIP(fno::launch_reduce_partials(part, nslots, p.Co, p.Ci, gW, gb, s));
   if (gx == nullptr && gR == nullptr) return FNO_OK;
   // gx = K(R^H) gz + W^T gz : the epilogue applies W transposed to gz, no bias, no activation
   fno::Epilogue ep{gz, p.Co, W, 1, p.Ci, nullptr, nullptr, 0};

@@ -56,9 +56,10 @@ hipError_t launch_zt_inv(const float2* a, float* out, const float2* twt, const f
                          Epilogue ep, float* tables, hipStream_t s);
 
 // gz = g * act'(z) (g = gout or the MSE gradient against a target), written to gz_out;
-// per-block partial sums of gb[o] and gW[o][i] into part[nblk][Co*Ci + Co] (double).
+// partial sums of gb[o] and gW[o][i] into part[*nslots][Co*Ci + Co] (double); *nslots (at most
+// bwd_pointwise_blocks()) is what launch_reduce_partials must be given.
 hipError_t launch_bwd_pointwise(const float* z, const float* gout, const float* x, float* gz_out,
-                                double* part, int nblk, int B, int Ci, int Co, int64_t N, int act,
+                                double* part, int* nslots, int B, int Ci, int Co, int64_t N, int act,
                                 int mse_target, double mse_scale, hipStream_t s);
 hipError_t launch_reduce_partials(const double* part, int nblk, int Co, int Ci, float* gW,
                                   float* gb, hipStream_t s);

@@ -895,6 +895,108 @@ __global__ __launch_bounds__(kThreads) void bwd_pointwise_kernel(
     if (tid + h * kThreads < npairs) part[(long long)blockIdx.x * npairs + tid + h * kThreads] = acc[h];
 }
 
+// Same step for widths that are a multiple of 4 (up to 20) and N a multiple of 64, streaming
+// and without LDS: lane (blk, j) of a wave owns channels j, 4+j, ... at the four consecutive
+// points 4*blk .. 4*blk+3 of a 64-point step, so every z / g / x access is a float4 and gz is
+// computed exactly once per element.  gW[o][i] = sum_p gz[o][p] x[i][p] is a dense contraction
+// over points and runs on the matrix cores: v_mfma_f32_4x4x1 block blk adds the outer product
+// gz[4To..4To+3][p] x[4Ti..4Ti+3][p] of its point p to its own 4x4 partial tile; the 16 blocks,
+// the waves and the thread blocks are summed at the end (per-wave partials in double, fixed order).
+__device__ __forceinline__ void gelu_and_grad_f(float z, float& val, float& grad) {
+  const float az = fabsf(z);
+  const float x = az * 0.70710678118654752440f;
+  float p = fmaf(x, 0.0000430638f, 0.0002765672f);
+  p = fmaf(x, p, 0.0001520143f);
+  p = fmaf(x, p, 0.0092705272f);
+  p = fmaf(x, p, 0.0422820123f);
+  p = fmaf(x, p, 0.0705230784f);
+  p = fmaf(x, p, 1.0f);
+  p = p * p; p = p * p; p = p * p; p = p * p;
+  const float erfx = 1.0f - __builtin_amdgcn_rcpf(p);              // erf(|z|/sqrt2), A&S 7.1.28
+  const float cdf = 0.5f + 0.5f * copysignf(erfx, z);
+  const float pdf = 0.39894228040143267794f * __expf(-0.5f * z * z);
+  val = z * cdf;
+  grad = fmaf(z, pdf, cdf);
+}
+
+template <int CT>
+__global__ __launch_bounds__(kThreads) void bwd_pointwise_mfma_kernel(
+    const float* __restrict__ z, const float* __restrict__ gout, const float* __restrict__ x,
+    float* __restrict__ gz_out, double* __restrict__ part, int B, long long N, int act, int mse_target,
+    float mse_scale) {
+  constexpr int C = 4 * CT;
+  const int tid = threadIdx.x;
+  const int lane = tid & 63, wave = tid >> 6;
+  const int j4 = lane & 3, blk = lane >> 2;
+  v4f acc[CT][CT];
+#pragma unroll
+  for (int a = 0; a < CT; ++a)
+#pragma unroll
+    for (int c = 0; c < CT; ++c) acc[a][c] = v4f{0.f, 0.f, 0.f, 0.f};
+  float gbacc[CT];
+#pragma unroll
+  for (int a = 0; a < CT; ++a) gbacc[a] = 0.f;
+
+  const long long steps_per_b = N >> 6;
+  const long long steps = steps_per_b * B;
+  const long long wave_id = (long long)blockIdx.x * (kThreads / 64) + wave;
+  const long long nwaves = (long long)gridDim.x * (kThreads / 64);
+  for (long long s = wave_id; s < steps; s += nwaves) {
+    const long long bb = s / steps_per_b;
+    const long long p0 = (s - bb * steps_per_b) * 64 + 4 * blk;
+    float4 gzv[CT], xv[CT];
+#pragma unroll
+    for (int T = 0; T < CT; ++T) {
+      const long long e = (bb * C + 4 * T + j4) * N + p0;
+      const float4 zv = *reinterpret_cast<const float4*>(z + e);
+      float4 g = *reinterpret_cast<const float4*>(gout + e);
+      xv[T] = *reinterpret_cast<const float4*>(x + e);
+      if (act) {
+        float v0, v1, v2, v3, d0, d1, d2, d3;
+        gelu_and_grad_f(zv.x, v0, d0); gelu_and_grad_f(zv.y, v1, d1);
+        gelu_and_grad_f(zv.z, v2, d2); gelu_and_grad_f(zv.w, v3, d3);
+        if (mse_target) g = make_float4(mse_scale * (v0 - g.x), mse_scale * (v1 - g.y),
+                                        mse_scale * (v2 - g.z), mse_scale * (v3 - g.w));
+        g = make_float4(g.x * d0, g.y * d1, g.z * d2, g.w * d3);
+      } else if (mse_target) {
+        g = make_float4(mse_scale * (zv.x - g.x), mse_scale * (zv.y - g.y), mse_scale * (zv.z - g.z),
+                        mse_scale * (zv.w - g.w));
+      }
+      *reinterpret_cast<float4*>(gz_out + e) = g;
+      gbacc[T] += (g.x + g.y) + (g.z + g.w);
+      gzv[T] = g;
+    }
+#pragma unroll
+    for (int a = 0; a < CT; ++a) {
+#pragma unroll
+      for (int c = 0; c < CT; ++c) {
+        acc[a][c] = __builtin_amdgcn_mfma_f32_4x4x1f32(gzv[a].x, xv[c].x, acc[a][c], 0, 0, 0);
+        acc[a][c] = __builtin_amdgcn_mfma_f32_4x4x1f32(gzv[a].y, xv[c].y, acc[a][c], 0, 0, 0);
+        acc[a][c] = __builtin_amdgcn_mfma_f32_4x4x1f32(gzv[a].z, xv[c].z, acc[a][c], 0, 0, 0);
+        acc[a][c] = __builtin_amdgcn_mfma_f32_4x4x1f32(gzv[a].w, xv[c].w, acc[a][c], 0, 0, 0);
+      }
+    }
+  }
+  // sum the 16 blocks of the wave (lanes with equal j4), then lanes 0..3 write the wave's partial
+  const int npairs = C * C + C;
+  double* dst = part + wave_id * npairs;
+#pragma unroll
+  for (int a = 0; a < CT; ++a) {
+#pragma unroll
+    for (int c = 0; c < CT; ++c) {
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        float v = acc[a][c][i];
+        v += __shfl_xor(v, 4); v += __shfl_xor(v, 8); v += __shfl_xor(v, 16); v += __shfl_xor(v, 32);
+        if (blk == 0) dst[(4 * a + i) * C + 4 * c + j4] = double(v);
+      }
+    }
+    float gsum = gbacc[a];
+    gsum += __shfl_xor(gsum, 4); gsum += __shfl_xor(gsum, 8); gsum += __shfl_xor(gsum, 16); gsum += __shfl_xor(gsum, 32);
+    if (blk == 0) dst[C * C + 4 * a + j4] = double(gsum);
+  }
+}
+
 __global__ void reduce_partials_kernel(const double* __restrict__ part, int nblk, int Co, int Ci,
                                        float* __restrict__ gW, float* __restrict__ gb) {
   const int q = blockIdx.x * blockDim.x + threadIdx.x;
@@ -1266,15 +1368,39 @@ hipError_t launch_zt_inv(const float2* a, float* out, const float2* twt, const f
   return hipGetLastError();
 }
 
+// number of partial-sum slots the workspace must hold (one per wave of the streaming kernel)
 int bwd_pointwise_blocks(int B, int64_t N) {
-  const int64_t tiles = (int64_t)B * ((N + kBwdTile - 1) / kBwdTile);
-  return (int)(tiles < 2048 ? tiles : 2048);
+  (void)B; (void)N;
+  return 4096;
 }
 
 hipError_t launch_bwd_pointwise(const float* z, const float* gout, const float* x, float* gz_out,
-                                double* part, int nblk, int B, int Ci, int Co, int64_t N, int act,
+                                double* part, int* nslots, int B, int Ci, int Co, int64_t N, int act,
                                 int mse_target, double mse_scale, hipStream_t s) {
   if (Co * Ci + Co > kBwdPairs * kThreads) return hipErrorInvalidValue;
+  const bool aligned = ((reinterpret_cast<uintptr_t>(z) | reinterpret_cast<uintptr_t>(gout) |
+                         reinterpret_cast<uintptr_t>(x) | reinterpret_cast<uintptr_t>(gz_out)) & 15) == 0;
+  if (Ci == Co && Co % 4 == 0 && Co <= 20 && N % 64 == 0 && aligned) {
+    const int64_t steps = (N / 64) * B;
+    int64_t nb = (steps + 3) / 4;
+    if (nb > 1024) nb = 1024;
+    *nslots = (int)nb * 4;
+    const dim3 grid((unsigned)nb);
+    switch (Co / 4) {
+#define FNO_BPW(CTV)                                                                               \
+  case CTV:                                                                                        \
+    hipLaunchKernelGGL((bwd_pointwise_mfma_kernel<CTV>), grid, dim3(kThreads), 0, s, z, gout, x,   \
+                       gz_out, part, B, (long long)N, act, mse_target, (float)mse_scale);          \
+    break;
+      FNO_BPW(1) FNO_BPW(2) FNO_BPW(3) FNO_BPW(4) FNO_BPW(5)
+#undef FNO_BPW
+      default: return hipErrorInvalidValue;
+    }
+    return hipGetLastError();
+  }
+  const int64_t tiles = (int64_t)B * ((N + kBwdTile - 1) / kBwdTile);
+  const int nblk = (int)(tiles < 2048 ? tiles : 2048);
+  *nslots = nblk;
   const size_t lds = (size_t)(Co + Ci) * (kBwdTile + 1) * 4;
   hipLaunchKernelGGL(bwd_pointwise_kernel, dim3((unsigned)nblk), dim3(kThreads), lds, s, z, gout,
                      x, gz_out, part, B, Ci, Co, (long long)N, act, mse_target, (float)mse_scale);
