@@ -300,11 +300,12 @@ __global__ __launch_bounds__(kThreads) void axis_fwd_kernel(
   float2* F = reinterpret_cast<float2*>(smem);          // [N][W]
   const int P = N / M;
   const int tid = threadIdx.x;
+  const int nthr = blockDim.x;
   const long long o = blockIdx.x / ncb;
   const long long c0 = (long long)(blockIdx.x % ncb) * W;
   const int wc = (int)min((long long)W, inner - c0);
 
-  for (int idx = tid; idx < P * W; idx += kThreads) {
+  for (int idx = tid; idx < P * W; idx += nthr) {
     const int col = idx % W, n2 = idx / W;
     if (col < wc) {
       const float2* src = in + (o * N + n2) * inner + c0 + col;
@@ -317,7 +318,7 @@ __global__ __launch_bounds__(kThreads) void axis_fwd_kernel(
     }
   }
   __syncthreads();
-  for (int idx = tid; idx < L * W; idx += kThreads) {
+  for (int idx = tid; idx < L * W; idx += nthr) {
     const int col = idx % W, j = idx / W;
     if (col < wc) {
       const int mj = posmod(kfreq(j, L, npos), M);
@@ -339,17 +340,18 @@ __global__ __launch_bounds__(kThreads) void axis_inv_kernel(
   float2* Y = reinterpret_cast<float2*>(smem);          // [L][W]
   const int P = N / M;
   const int tid = threadIdx.x;
+  const int nthr = blockDim.x;
   const long long o = blockIdx.x / ncb;
   const long long c0 = (long long)(blockIdx.x % ncb) * W;
   const int wc = (int)min((long long)W, inner - c0);
   const int kmin = npos - L, kmax = npos - 1;
 
-  for (int idx = tid; idx < L * W; idx += kThreads) {
+  for (int idx = tid; idx < L * W; idx += nthr) {
     const int col = idx % W, j = idx / W;
     if (col < wc) Y[idx] = in[(o * L + j) * inner + c0 + col];
   }
   __syncthreads();
-  for (int idx = tid; idx < P * W; idx += kThreads) {
+  for (int idx = tid; idx < P * W; idx += nthr) {
     const int col = idx % W, n2 = idx / W;
     if (col < wc) {
       float2 g[M];
@@ -380,28 +382,42 @@ __device__ __forceinline__ float mode_scale(long long k, int mt, int Nt, float i
 }
 
 constexpr int kMixB = 4;   // batch entries held per pass
+constexpr int kMixO = 4;   // output channels per thread in the forward mix
 
 __global__ __launch_bounds__(kThreads) void mix_fwd_kernel(
     const float2* __restrict__ xh, const float2* __restrict__ R, float2* __restrict__ yh, int B,
     int Ci, int Co, long long K, int mt, int Nt, float invN) {
+  // one thread: one mode, kMixO output channels, kMixB batch entries; R is read exactly once
   const long long k = (long long)blockIdx.x * kThreads + threadIdx.x;
-  const int o = blockIdx.y;
+  const int o0 = blockIdx.y * kMixO;
   if (k >= K) return;
   const float sc = mode_scale(k, mt, Nt, invN);
   for (int b0 = 0; b0 < B; b0 += kMixB) {
-    float2 acc[kMixB];
+    float2 acc[kMixB][kMixO];
 #pragma unroll
-    for (int u = 0; u < kMixB; ++u) acc[u] = make_float2(0.f, 0.f);
+    for (int u = 0; u < kMixB; ++u)
+#pragma unroll
+      for (int v = 0; v < kMixO; ++v) acc[u][v] = make_float2(0.f, 0.f);
     for (int i = 0; i < Ci; ++i) {
-      const float2 r = R[((long long)i * Co + o) * K + k];
+      float2 xv[kMixB];
 #pragma unroll
       for (int u = 0; u < kMixB; ++u)
-        if (b0 + u < B) acc[u] = cfma(xh[((long long)(b0 + u) * Ci + i) * K + k], r, acc[u]);
+        xv[u] = (b0 + u < B) ? xh[((long long)(b0 + u) * Ci + i) * K + k] : make_float2(0.f, 0.f);
+#pragma unroll
+      for (int v = 0; v < kMixO; ++v) {
+        if (o0 + v < Co) {
+          const float2 r = R[((long long)i * Co + o0 + v) * K + k];
+#pragma unroll
+          for (int u = 0; u < kMixB; ++u) acc[u][v] = cfma(xv[u], r, acc[u][v]);
+        }
+      }
     }
 #pragma unroll
     for (int u = 0; u < kMixB; ++u)
-      if (b0 + u < B)
-        yh[((long long)(b0 + u) * Co + o) * K + k] = make_float2(acc[u].x * sc, acc[u].y * sc);
+#pragma unroll
+      for (int v = 0; v < kMixO; ++v)
+        if (b0 + u < B && o0 + v < Co)
+          yh[((long long)(b0 + u) * Co + o0 + v) * K + k] = make_float2(acc[u][v].x * sc, acc[u][v].y * sc);
   }
 }
 
@@ -1079,12 +1095,19 @@ size_t zt_inv_lds(AxisPlan az, int Nt, int mt, int Co) {
   return (size_t)Co * Rz * ((size_t)mt * 8 + (size_t)(Nt + 1) * 4);
 }
 
-int axis_cols(AxisPlan ax, int64_t inner) {
-  int w = 16;
-  while (w > 1 && (size_t)ax.N * w * 8 > (size_t)kLdsBudget) w >>= 1;
+int axis_cols(AxisPlan ax, int64_t inner, int rows, int wmax) {
+  // widest column tile whose [rows][w] complex tile stays within 32 KiB of LDS
+  int w = wmax;
+  while (w > 1 && (size_t)rows * w * 8 > (size_t)(32 * 1024)) w >>= 1;
   while (w > 1 && (w >> 1) >= inner) w >>= 1;
   return w;
 }
+
+int axis_threads(int items) {
+  int t = ((items + 63) / 64) * 64;
+  return t < 64 ? 64 : (t > kThreads ? kThreads : t);
+}
+
 
 #define FNO_DISPATCH_M(Mval, CALL)                \
   switch (Mval) {                                 \
@@ -1103,7 +1126,7 @@ bool tz_fwd_fits(AxisPlan az, int Nt, int mt) { return tz_fwd_lds(az, Nt, mt, 1)
 bool zt_inv_fits(AxisPlan az, int Nt, int mt, int Co) {
   return Co <= kMaxCo && zt_inv_lds(az, Nt, mt, Co) <= (size_t)(64 * 1024);
 }
-bool axis_fits(AxisPlan ax) { return (size_t)ax.N * 8 <= (size_t)kLdsBudget; }
+bool axis_fits(AxisPlan ax) { return (size_t)ax.N * 8 <= (size_t)(32 * 1024); }
 int mfma_q_nw(AxisPlan az, int Nt, int nw);
 int mfma_nw(AxisPlan az, int Nt, int mt, int Co, int Cu);
 size_t zt_mfma_lds(AxisPlan az, int Nt, int mt, int Co, int Cu, int q);
@@ -1188,7 +1211,7 @@ hipError_t launch_tz_fwd(const float* x, float2* out, const float2* twt, const f
 hipError_t launch_axis_fwd(const float2* in, float2* out, const float2* tw, int64_t outer,
                            AxisPlan ax, int64_t inner, hipStream_t s) {
   if (outer <= 0 || inner <= 0) return hipSuccess;
-  const int W = axis_cols(ax, inner);
+  const int W = axis_cols(ax, inner, ax.N, 16);
   const int64_t ncb = (inner + W - 1) / W;
   const int64_t nblk = outer * ncb;
   if (nblk > 0x7fffffffLL || ncb > 0x7fffffffLL) return hipErrorInvalidValue;
@@ -1202,13 +1225,14 @@ hipError_t launch_axis_fwd(const float2* in, float2* out, const float2* tw, int6
 hipError_t launch_axis_inv(const float2* in, float2* out, const float2* tw, int64_t outer,
                            AxisPlan ax, int64_t inner, hipStream_t s) {
   if (outer <= 0 || inner <= 0) return hipSuccess;
-  const int W = axis_cols(ax, inner);
+  const int W = axis_cols(ax, inner, ax.L, 32);
   const int64_t ncb = (inner + W - 1) / W;
   const int64_t nblk = outer * ncb;
   if (nblk > 0x7fffffffLL || ncb > 0x7fffffffLL) return hipErrorInvalidValue;
   const size_t lds = (size_t)ax.L * W * 8;
+  const int thr = axis_threads(ax.P * W);
   FNO_DISPATCH_M(ax.M, hipLaunchKernelGGL((axis_inv_kernel<MM>), dim3((unsigned)nblk),
-                                          dim3(kThreads), lds, s, in, out, tw, ax.N, ax.L, ax.npos,
+                                          dim3(thr), lds, s, in, out, tw, ax.N, ax.L, ax.npos,
                                           (long long)inner, W, (int)ncb));
   return hipGetLastError();
 }
@@ -1217,7 +1241,7 @@ hipError_t launch_mix_fwd(const float2* xh, const float2* R, float2* yh, int B, 
                           int64_t K, int mt, int Nt, double invN, hipStream_t s) {
   const int64_t nb = (K + kThreads - 1) / kThreads;
   if (nb > 0x7fffffffLL || Co > 65535) return hipErrorInvalidValue;
-  hipLaunchKernelGGL(mix_fwd_kernel, dim3((unsigned)nb, (unsigned)Co), dim3(kThreads), 0, s, xh, R,
+  hipLaunchKernelGGL(mix_fwd_kernel, dim3((unsigned)nb, (unsigned)((Co + kMixO - 1) / kMixO)), dim3(kThreads), 0, s, xh, R,
                      yh, B, Ci, Co, (long long)K, mt, Nt, (float)invN);
   return hipGetLastError();
 }

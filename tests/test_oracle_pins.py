@@ -428,3 +428,22 @@ def test_separable_weight_grads_match_block_bwd():
     ref = O.block_bwd(x, r, w, np.zeros(3), g, spec, "identity")
     gw, gb = O.separable_weight_grads(fg, fx)
     assert _rel(gw, ref["gW"]) < 1e-13 and _rel(gb, ref["gb"]) < 1e-13
+
+
+def test_oracle_reproduces_its_frozen_fixture():
+    """tests/golden/block_small.txt was written by tests/golden/make_golden.py from the oracle alone."""
+    import importlib.util
+    import os
+    here = os.path.dirname(os.path.abspath(__file__))
+    spec_ = importlib.util.spec_from_file_location("make_golden", os.path.join(here, "golden", "make_golden.py"))
+    mod = importlib.util.module_from_spec(spec_)
+    spec_.loader.exec_module(mod)
+    stored = {}
+    for line in open(os.path.join(here, "golden", "block_small.txt")):
+        if not line.startswith("#"):
+            name, val = line.rstrip("\n").split("\t")
+            stored[name] = float(val)
+    got = dict(mod.values())
+    assert set(got) == set(stored)
+    for name, v in got.items():
+        assert abs(float(v) - stored[name]) <= 1e-12 * max(1.0, abs(stored[name])), name
