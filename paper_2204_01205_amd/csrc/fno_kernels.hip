@@ -295,9 +295,10 @@ __global__ __launch_bounds__(kThreads) void tz_fwd_fast_kernel(
 template <int M>
 __global__ __launch_bounds__(kThreads) void axis_fwd_kernel(
     const float2* __restrict__ in, float2* __restrict__ out, const float2* __restrict__ tw, int N,
-    int L, int npos, long long inner, int W, int ncb) {
+    int L, int npos, long long inner, int W, int ncb, int tw_lds) {
   HIP_DYNAMIC_SHARED(float, smem)
   float2* F = reinterpret_cast<float2*>(smem);          // [N][W]
+  float2* TWs = F + N * W;                              // [L][P], only when tw_lds
   const int P = N / M;
   const int tid = threadIdx.x;
   const int nthr = blockDim.x;
@@ -305,6 +306,8 @@ __global__ __launch_bounds__(kThreads) void axis_fwd_kernel(
   const long long c0 = (long long)(blockIdx.x % ncb) * W;
   const int wc = (int)min((long long)W, inner - c0);
 
+  if (tw_lds)
+    for (int idx = tid; idx < L * P; idx += nthr) TWs[idx] = tw[idx];
   for (int idx = tid; idx < P * W; idx += nthr) {
     const int col = idx % W, n2 = idx / W;
     if (col < wc) {
@@ -323,7 +326,7 @@ __global__ __launch_bounds__(kThreads) void axis_fwd_kernel(
     if (col < wc) {
       const int mj = posmod(kfreq(j, L, npos), M);
       const float2* base = F + (P * mj) * W + col;
-      const float2* w = tw + j * P;
+      const float2* w = (tw_lds ? TWs : tw) + j * P;
       float2 acc = make_float2(0.f, 0.f);
       for (int n2 = 0; n2 < P; ++n2) acc = cfma(w[n2], base[n2 * W], acc);
       out[(o * L + j) * inner + c0 + col] = acc;
@@ -335,9 +338,11 @@ __global__ __launch_bounds__(kThreads) void axis_fwd_kernel(
 template <int M>
 __global__ __launch_bounds__(kThreads) void axis_inv_kernel(
     const float2* __restrict__ in, float2* __restrict__ out, const float2* __restrict__ tw, int N,
-    int L, int npos, long long inner, int W, int ncb) {
+    int L, int npos, long long inner, int W, int ncb, int tw_lds) {
   HIP_DYNAMIC_SHARED(float, smem)
   float2* Y = reinterpret_cast<float2*>(smem);          // [L][W]
+  float2* TWs = Y + L * W;                              // [L][P], only when tw_lds
+  const float2* twp = tw_lds ? TWs : tw;
   const int P = N / M;
   const int tid = threadIdx.x;
   const int nthr = blockDim.x;
@@ -346,6 +351,8 @@ __global__ __launch_bounds__(kThreads) void axis_inv_kernel(
   const int wc = (int)min((long long)W, inner - c0);
   const int kmin = npos - L, kmax = npos - 1;
 
+  if (tw_lds)
+    for (int idx = tid; idx < L * P; idx += nthr) TWs[idx] = tw[idx];
   for (int idx = tid; idx < L * W; idx += nthr) {
     const int col = idx % W, j = idx / W;
     if (col < wc) Y[idx] = in[(o * L + j) * inner + c0 + col];
@@ -360,7 +367,7 @@ __global__ __launch_bounds__(kThreads) void axis_inv_kernel(
         float2 acc = make_float2(0.f, 0.f);
         for (int k = kmin + posmod(m - kmin, M); k <= kmax; k += M) {
           const int j = k >= 0 ? k : k + L;
-          acc = cfmac(Y[j * W + col], tw[j * P + n2], acc);
+          acc = cfmac(Y[j * W + col], twp[j * P + n2], acc);
         }
         g[m] = acc;
       }
@@ -1215,10 +1222,12 @@ hipError_t launch_axis_fwd(const float2* in, float2* out, const float2* tw, int6
   const int64_t ncb = (inner + W - 1) / W;
   const int64_t nblk = outer * ncb;
   if (nblk > 0x7fffffffLL || ncb > 0x7fffffffLL) return hipErrorInvalidValue;
-  const size_t lds = (size_t)ax.N * W * 8;
+  // the twiddles go to LDS only when that does not cost a resident block
+  const int tw_lds = (size_t)ax.L * ax.P * 8 <= (size_t)(8 * 1024) && (size_t)ax.N * W * 8 <= (size_t)(16 * 1024);
+  const size_t lds = (size_t)ax.N * W * 8 + (tw_lds ? (size_t)ax.L * ax.P * 8 : 0);
   FNO_DISPATCH_M(ax.M, hipLaunchKernelGGL((axis_fwd_kernel<MM>), dim3((unsigned)nblk),
                                           dim3(kThreads), lds, s, in, out, tw, ax.N, ax.L, ax.npos,
-                                          (long long)inner, W, (int)ncb));
+                                          (long long)inner, W, (int)ncb, tw_lds));
   return hipGetLastError();
 }
 
@@ -1229,11 +1238,12 @@ hipError_t launch_axis_inv(const float2* in, float2* out, const float2* tw, int6
   const int64_t ncb = (inner + W - 1) / W;
   const int64_t nblk = outer * ncb;
   if (nblk > 0x7fffffffLL || ncb > 0x7fffffffLL) return hipErrorInvalidValue;
-  const size_t lds = (size_t)ax.L * W * 8;
+  const int tw_lds = (size_t)ax.L * ax.P * 8 <= (size_t)(8 * 1024);
+  const size_t lds = (size_t)ax.L * W * 8 + (tw_lds ? (size_t)ax.L * ax.P * 8 : 0);
   const int thr = axis_threads(ax.P * W);
   FNO_DISPATCH_M(ax.M, hipLaunchKernelGGL((axis_inv_kernel<MM>), dim3((unsigned)nblk),
                                           dim3(thr), lds, s, in, out, tw, ax.N, ax.L, ax.npos,
-                                          (long long)inner, W, (int)ncb));
+                                          (long long)inner, W, (int)ncb, tw_lds));
   return hipGetLastError();
 }
 
