@@ -146,7 +146,9 @@ def main():
     stage_launches = {k: len(v) / args.steps for k, v in stage_ms.items()}
     dominant = max(stage_avg, key=stage_avg.get)
     # algorithmic bytes per launch of each full-grid sweep: 4 B per point-channel per tensor touched
-    alg_bytes = {"zt_inv": 8.0 * pc,      # reads x for W x, writes out (pruned spectrum not counted)
+    # zt_inv reads the tensor W acts on and writes the result (pruned spectrum not counted); in a
+    # training step the forward launch also writes z, and the figure is the mean of its two launches
+    alg_bytes = {"zt_inv": 10.0 * pc if train else 8.0 * pc,
                  "tz_fwd": 4.0 * pc,      # reads x
                  "bwd_pointwise": 16.0 * pc}   # reads z, target, x; writes gz
     dom_bytes = alg_bytes.get(dominant, 0.0)

@@ -1020,15 +1020,38 @@ __global__ __launch_bounds__(kThreads) void bwd_pointwise_mfma_kernel(
   }
 }
 
-__global__ void reduce_partials_kernel(const double* __restrict__ part, int nblk, int Co, int Ci,
-                                       float* __restrict__ gW, float* __restrict__ gb) {
-  const int q = blockIdx.x * blockDim.x + threadIdx.x;
+// Sum of the partial slots in a fixed order (same bits on every run): 64 pairs per block, the
+// slots dealt round-robin to kRedGroups threads per pair, whose sums are added in group order.
+constexpr int kRedGroups = 16;
+__global__ __launch_bounds__(64 * kRedGroups) void reduce_partials_kernel(
+    const double* __restrict__ part, int nblk, int Co, int Ci, float* __restrict__ gW,
+    float* __restrict__ gb) {
+  __shared__ double sums[kRedGroups][64];
+  const int lane = threadIdx.x & 63, grp = threadIdx.x >> 6;
+  const int q = blockIdx.x * 64 + lane;
   const int npairs = Co * Ci + Co;
-  if (q >= npairs) return;
   double s = 0.0;
-  for (int blk = 0; blk < nblk; ++blk) s += part[(long long)blk * npairs + q];
-  if (q < Co * Ci) { if (gW != nullptr) gW[q] = float(s); }
-  else if (gb != nullptr) gb[q - Co * Ci] = float(s);
+  if (q < npairs) {
+    const double* p = part + q;
+    int blk = grp;
+    for (; blk + 7 * kRedGroups < nblk; blk += 8 * kRedGroups) {
+      double v[8];
+#pragma unroll
+      for (int u = 0; u < 8; ++u) v[u] = p[(long long)(blk + u * kRedGroups) * npairs];
+#pragma unroll
+      for (int u = 0; u < 8; ++u) s += v[u];
+    }
+    for (; blk < nblk; blk += kRedGroups) s += p[(long long)blk * npairs];
+  }
+  sums[grp][lane] = s;
+  __syncthreads();
+  if (grp == 0 && q < npairs) {
+    double t = 0.0;
+#pragma unroll
+    for (int g = 0; g < kRedGroups; ++g) t += sums[g][lane];
+    if (q < Co * Ci) { if (gW != nullptr) gW[q] = float(t); }
+    else if (gb != nullptr) gb[q - Co * Ci] = float(t);
+  }
 }
 
 // ------------------------------------------------------------------------------------------
@@ -1444,8 +1467,8 @@ hipError_t launch_bwd_pointwise(const float* z, const float* gout, const float* 
 hipError_t launch_reduce_partials(const double* part, int nblk, int Co, int Ci, float* gW,
                                   float* gb, hipStream_t s) {
   const int npairs = Co * Ci + Co;
-  hipLaunchKernelGGL(reduce_partials_kernel, dim3((npairs + 63) / 64), dim3(64), 0, s, part, nblk,
-                     Co, Ci, gW, gb);
+  hipLaunchKernelGGL(reduce_partials_kernel, dim3((npairs + 63) / 64), dim3(64 * kRedGroups), 0, s, part,
+                     nblk, Co, Ci, gW, gb);
   return hipGetLastError();
 }
 
