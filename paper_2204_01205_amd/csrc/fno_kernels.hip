@@ -428,41 +428,59 @@ __global__ __launch_bounds__(kThreads) void mix_fwd_kernel(
   }
 }
 
+// One thread: one mode k, kMixI input channels, the batch in chunks of kMixB; the gradient
+// spectrum gh is then read once per kMixI input channels.
+constexpr int kMixI = 4;
 __global__ __launch_bounds__(kThreads) void mix_bwd_kernel(
     const float2* __restrict__ xh, const float2* __restrict__ R, const float2* __restrict__ gh,
     float2* __restrict__ gR, float2* __restrict__ gxh, int B, int Ci, int Co, long long K, int mt,
     int Nt, float invN) {
   const long long k = (long long)blockIdx.x * kThreads + threadIdx.x;
-  const int i = blockIdx.y;
+  const int i0 = blockIdx.y * kMixI;
   if (k >= K) return;
   const float sc = mode_scale(k, mt, Nt, invN);
   for (int b0 = 0; b0 < B; b0 += kMixB) {
-    float2 xv[kMixB], gx[kMixB];
+    float2 xv[kMixB][kMixI], gx[kMixB][kMixI];
 #pragma unroll
-    for (int u = 0; u < kMixB; ++u) {
-      gx[u] = make_float2(0.f, 0.f);
-      xv[u] = (b0 + u < B) ? xh[((long long)(b0 + u) * Ci + i) * K + k] : make_float2(0.f, 0.f);
-    }
+    for (int u = 0; u < kMixB; ++u)
+#pragma unroll
+      for (int v = 0; v < kMixI; ++v) {
+        gx[u][v] = make_float2(0.f, 0.f);
+        xv[u][v] = (b0 + u < B && i0 + v < Ci) ? xh[((long long)(b0 + u) * Ci + i0 + v) * K + k]
+                                               : make_float2(0.f, 0.f);
+      }
     for (int o = 0; o < Co; ++o) {
-      const long long ridx = ((long long)i * Co + o) * K + k;
-      const float2 r = R[ridx];
-      float2 gr = make_float2(0.f, 0.f);
-      if (gR != nullptr && b0 > 0) gr = gR[ridx];
+      float2 r[kMixI], gr[kMixI], gy[kMixB];
+#pragma unroll
+      for (int v = 0; v < kMixI; ++v) {
+        const long long ridx = ((long long)(i0 + v) * Co + o) * K + k;
+        r[v] = i0 + v < Ci ? R[ridx] : make_float2(0.f, 0.f);
+        gr[v] = (gR != nullptr && b0 > 0 && i0 + v < Ci) ? gR[ridx] : make_float2(0.f, 0.f);
+      }
 #pragma unroll
       for (int u = 0; u < kMixB; ++u) {
-        if (b0 + u < B) {
-          float2 gy = gh[((long long)(b0 + u) * Co + o) * K + k];
-          gy.x *= sc; gy.y *= sc;
-          gr = cfmac(gy, xv[u], gr);        // conj(xh) * gy
-          gx[u] = cfmac(gy, r, gx[u]);      // conj(R) * gy
-        }
+        gy[u] = b0 + u < B ? gh[((long long)(b0 + u) * Co + o) * K + k] : make_float2(0.f, 0.f);
+        gy[u].x *= sc; gy[u].y *= sc;
       }
-      if (gR != nullptr) gR[ridx] = gr;
+#pragma unroll
+      for (int u = 0; u < kMixB; ++u)
+#pragma unroll
+        for (int v = 0; v < kMixI; ++v) {
+          gr[v] = cfmac(gy[u], xv[u][v], gr[v]);        // conj(xh) * gy
+          gx[u][v] = cfmac(gy[u], r[v], gx[u][v]);      // conj(R) * gy
+        }
+      if (gR != nullptr) {
+#pragma unroll
+        for (int v = 0; v < kMixI; ++v)
+          if (i0 + v < Ci) gR[((long long)(i0 + v) * Co + o) * K + k] = gr[v];
+      }
     }
     if (gxh != nullptr) {
 #pragma unroll
       for (int u = 0; u < kMixB; ++u)
-        if (b0 + u < B) gxh[((long long)(b0 + u) * Ci + i) * K + k] = gx[u];
+#pragma unroll
+        for (int v = 0; v < kMixI; ++v)
+          if (b0 + u < B && i0 + v < Ci) gxh[((long long)(b0 + u) * Ci + i0 + v) * K + k] = gx[u][v];
     }
   }
 }
@@ -1283,8 +1301,8 @@ hipError_t launch_mix_bwd(const float2* xh, const float2* R, const float2* gh, f
                           float2* gxh, int B, int Ci, int Co, int64_t K, int mt, int Nt,
                           double invN, hipStream_t s) {
   const int64_t nb = (K + kThreads - 1) / kThreads;
-  if (nb > 0x7fffffffLL || Ci > 65535) return hipErrorInvalidValue;
-  hipLaunchKernelGGL(mix_bwd_kernel, dim3((unsigned)nb, (unsigned)Ci), dim3(kThreads), 0, s, xh, R,
+  if (nb > 0x7fffffffLL || Ci > 4 * 65535) return hipErrorInvalidValue;
+  hipLaunchKernelGGL(mix_bwd_kernel, dim3((unsigned)nb, (unsigned)((Ci + kMixI - 1) / kMixI)), dim3(kThreads), 0, s, xh, R,
                      gh, gR, gxh, B, Ci, Co, (long long)K, mt, Nt, (float)invN);
   return hipGetLastError();
 }
