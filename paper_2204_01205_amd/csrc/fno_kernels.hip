@@ -607,11 +607,12 @@ typedef float v4f __attribute__((ext_vector_type(4)));
 
 
 // Tables of the matrix-core inverse kernel, one blob per residue group g in the kernel's LDS
-// layout: cos / -sin rows [2 mt][NT], W transposed and padded [Cu][CP], z twiddles [Q][Lz].
+// layout: cos / -sin rows [2 mt][NT], W transposed and padded [Cu][CP], z twiddles [Q][Lz],
+// bias padded [CP].
 __global__ void zt_tables_kernel(float* __restrict__ blob, const float2* __restrict__ twt,
                                  const float2* __restrict__ twz, const float* __restrict__ W, int w_so,
-                                 int w_si, int Co, int Cu, int CP, int mt, int NT, int Lz, int Pz, int Q,
-                                 int blob_floats) {
+                                 int w_si, const float* __restrict__ bias, int Co, int Cu, int CP, int mt,
+                                 int NT, int Lz, int Pz, int Q, int blob_floats) {
   const int g = blockIdx.x;
   float* dst = blob + (long long)g * blob_floats;
   const int n_cs = 2 * mt * NT, n_wt = (W != nullptr) ? Cu * CP : 0, n_tw = 2 * Q * Lz;
@@ -630,6 +631,9 @@ __global__ void zt_tables_kernel(float* __restrict__ blob, const float2* __restr
       const int c = e >> 1, q = c / Lz, j = c - q * Lz;
       const float2 w = twz[j * Pz + g * Q + q];
       v = (e & 1) ? w.y : w.x;
+    } else if (idx < n_cs + n_wt + n_tw + CP) {
+      const int o = idx - n_cs - n_wt - n_tw;
+      v = (bias != nullptr && o < Co) ? bias[o] : 0.f;
     }
     dst[idx] = v;
   }
@@ -868,6 +872,198 @@ __global__ __launch_bounds__(64 * NW, NW == 8 ? 4 : (CT >= 8 ? 2 : 3)) void zt_i
         for (int sl = 0; sl < 2; ++sl)
           *reinterpret_cast<float4*>(op + (4 * T) * Npts + poff[sl]) =
               make_float4(acc[T][sl][0], acc[T][sl][1], acc[T][sl][2], acc[T][sl][3]);
+      }
+    }
+  }
+}
+
+// Column variant of the matrix-core inverse kernel for NT = 32, MZ = 16: one block of eight waves
+// owns a whole (b,nx,ny) column, stages the column's spectrum once and walks the residue classes
+// of z two at a time (a tile of 32 rows x 32 t per step, Pz / 2 steps).  The spectrum A stays in
+// LDS for all steps; V holds one residue class (16 rows) at a time, so a step is two half steps
+// (z stage, t stage, W part, epilogue), one per slot of u registers.  Slot s of lane block (wave, blk) is the quad
+// blk % 8 of row z = Pz (2 wave + blk / 8) + 2 step + s.  Launch: grid (NxNy, B), 512 threads.
+// The table blob is the one of zt_tables_kernel with Q = Pz (all twiddles, [Pz][Lz]).
+template <int CT, bool FULL>
+__global__ __launch_bounds__(512, 4) void zt_inv_col_kernel(
+    const float2* __restrict__ a, float* __restrict__ out, int Co_rt, int NxNy, int Nz, int Lz,
+    int nposz, int mt, int inv_mt, int a_floats, int a_stride4, int v_stride,
+    const float* __restrict__ blob, int blob_floats, EpiArgs ep) {
+  HIP_DYNAMIC_SHARED(float, smem)
+  constexpr int NT = 32, MZ = 16, NW = 8;
+  constexpr int CP = 4 * CT;
+  constexpr int CI = CP;
+  constexpr int nthr = 64 * NW;
+  const int Co = FULL ? CP : Co_rt;
+  const int Cu = FULL ? CI : ep.Cu;
+  const int Pz = Nz / MZ;
+  const float2* A = reinterpret_cast<const float2*>(smem);      // [Co][Lz][mt], padded channel stride
+  float2* V = reinterpret_cast<float2*>(smem + a_floats);       // [CP][MZ][mt], padded channel stride
+  float* CS = smem + a_floats + 2 * CP * v_stride;              // [2 mt][NT]: cos rows and -sin rows
+  float* Wt = CS + 2 * mt * NT;                                 // [Cu][CP]
+  const bool lin = ep.u != nullptr;
+  const float2* TW = reinterpret_cast<const float2*>(Wt + (lin ? Cu * CP : 0));   // [Pz][Lz]
+  const int tid = threadIdx.x;
+  const int xy = blockIdx.x;
+  const long long b = blockIdx.y;
+  const int lane = tid & 63, wave = tid >> 6;
+  const int j4 = lane & 3;                    // t within the quad (A side) / channel within the tile (B, D side)
+  const int blk = lane >> 2;
+  const int quad = blk & 7;
+  const int n1 = 2 * wave + (blk >> 3);       // row of this lane block inside a residue class
+  const long long Npts = (long long)NxNy * Nz * NT;
+  const long long pbase = ((long long)xy * Nz + Pz * n1) * NT + 4 * quad;   // + (2 step + slot) * NT
+  const int kmin = nposz - Lz, kmax = nposz - 1;
+  const int mbase = posmod(-kmin, MZ);
+  const int nitems = Co * mt;                 // z-stage items of one residue class: (channel, kt)
+
+  for (int c0 = wave * 256; c0 < blob_floats; c0 += 256 * NW)
+    __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(blob + c0 + 4 * lane),
+                                     (__attribute__((address_space(3))) void*)(CS + c0), 16, 0, 0);
+  {
+    const int per_ch4 = (Lz * mt) >> 1;                  // float4 pieces per channel
+    const float2* abase = a + ((b * Co) * NxNy + xy) * (long long)(Lz * mt);
+    const long long astride = (long long)NxNy * Lz * mt; // float2 between channels
+    for (int o = wave; o < Co; o += NW) {
+      for (int c0 = 0; c0 < per_ch4; c0 += 64) {
+        const int f = c0 + lane;
+        if (f < per_ch4)
+          __builtin_amdgcn_global_load_lds(
+              (const __attribute__((address_space(1))) void*)(abase + o * astride + 2 * f),
+              (__attribute__((address_space(3))) void*)(smem + 4 * (o * a_stride4 + c0)), 16, 0, 0);
+      }
+    }
+  }
+  // this thread's z-stage item
+  const int zo = (tid * inv_mt) >> 16;
+  const int zkt = tid - zo * mt;
+  const float2* asrc = A + zo * (2 * a_stride4) + zkt;
+  float2* vdst = V + zo * v_stride + zkt;
+  if (!FULL) {
+    // channels of the padding tiles: finite values so the unused MFMA columns stay harmless
+    for (int idx = tid; idx < (CP - Co) * v_stride; idx += nthr) V[Co * v_stride + idx] = make_float2(0.f, 0.f);
+  }
+  const float* BI = reinterpret_cast<const float*>(TW + Pz * Lz);      // bias, padded to CP
+  // u values of the two slots (lane 4b+i takes t = 4 quad + i): loaded one step ahead, each
+  // slot's registers refilled as soon as its W part has used them
+  float xv[CI][2];
+  const float* ubase = lin ? ep.u + (b * Cu) * Npts + j4 + pbase : nullptr;
+  asm volatile("" ::: "memory");    // keep the issue order: tables, spectrum, u
+  if (lin) {
+#pragma unroll
+    for (int sl = 0; sl < 2; ++sl)
+#pragma unroll
+      for (int i = 0; i < CI; ++i)
+        if (FULL || i < Cu) xv[i][sl] = ubase[i * Npts + sl * NT];
+  }
+  asm volatile("" ::: "memory");
+  // tables and spectrum have landed once at most the u loads, issued after them, are
+  // outstanding (the counter retires in order; vmcnt sits in bits 3:0 and 15:14)
+  if constexpr (FULL && 2 * CI < 64) {
+    constexpr int n = 2 * CI;
+    if (lin) __builtin_amdgcn_s_waitcnt(((n >> 4) << 14) | 0x0F70 | (n & 15));
+    else __builtin_amdgcn_s_waitcnt(0x0F70);
+  } else {
+    __builtin_amdgcn_s_waitcnt(0x0F70);
+  }
+  __syncthreads();
+
+  const int nsteps = Pz >> 1;
+  for (int step = 0; step < nsteps; ++step) {
+#pragma unroll
+    for (int sl = 0; sl < 2; ++sl) {
+      const int n2 = 2 * step + sl;                       // residue class of this half step
+      const long long poff = pbase + (long long)n2 * NT;  // this lane block's quad in a channel
+      // z stage: item (o, kt) collects the kept z-frequencies with their twiddles into MZ bins;
+      // an inverse FFT over n1 gives the rows z = Pz n1 + n2
+      if (tid < nitems) {
+        const float2* twq = TW + n2 * Lz;
+        float2 gres[MZ];
+#pragma unroll
+        for (int m = 0; m < MZ; ++m) {
+          float2 accb = make_float2(0.f, 0.f);
+          for (int k = kmin + ((m + mbase) & (MZ - 1)); k <= kmax; k += MZ) {
+            const int j = k >= 0 ? k : k + Lz;
+            accb = cfmac(asrc[j * mt], twq[j], accb);
+          }
+          gres[m] = accb;
+        }
+        fft_reg<MZ, +1>(gres);
+#pragma unroll
+        for (int r = 0; r < MZ; ++r) vdst[r * mt] = gres[bitrev<MZ>(r)];
+      }
+      __syncthreads();
+      // t stage: complex-to-real step over kt on the matrix cores
+      v4f acc[CT];
+#pragma unroll
+      for (int T = 0; T < CT; ++T) {
+        const float bv = BI[4 * T + j4];
+        acc[T] = v4f{bv, bv, bv, bv};
+      }
+      const float* cs_lane = CS + 4 * quad + j4;
+      const float2* v0 = V + j4 * v_stride + n1 * mt;
+      for (int kt = 0; kt < mt; ++kt) {
+        const float c = cs_lane[(2 * kt) * NT];
+        const float sn = cs_lane[(2 * kt + 1) * NT];
+        float2 va[CT];
+#pragma unroll
+        for (int T = 0; T < CT; ++T) va[T] = v0[4 * T * v_stride + kt];
+#pragma unroll
+        for (int T = 0; T < CT; ++T) {
+          acc[T] = __builtin_amdgcn_mfma_f32_4x4x1f32(c, va[T].x, acc[T], 0, 0, 0);
+          acc[T] = __builtin_amdgcn_mfma_f32_4x4x1f32(sn, va[T].y, acc[T], 0, 0, 0);
+        }
+      }
+      __syncthreads();      // V is rewritten by the next z stage
+      if (lin) {
+        constexpr int IB = 4;                       // input channels per batch of LDS reads
+#pragma unroll
+        for (int i0 = 0; i0 < CI; i0 += IB) {
+          float wv[IB][CT];
+#pragma unroll
+          for (int ii = 0; ii < IB; ++ii)
+#pragma unroll
+            for (int T = 0; T < CT; ++T)
+              wv[ii][T] = (FULL || i0 + ii < Cu) ? Wt[(i0 + ii) * CP + 4 * T + j4] : 0.f;
+#pragma unroll
+          for (int ii = 0; ii < IB; ++ii) {
+            if (FULL || i0 + ii < Cu) {
+#pragma unroll
+              for (int T = 0; T < CT; ++T)
+                acc[T] = __builtin_amdgcn_mfma_f32_4x4x1f32(xv[i0 + ii][sl], wv[ii][T], acc[T], 0, 0, 0);
+            }
+          }
+        }
+        // this slot's u values of the next step
+        asm volatile("" ::: "memory");
+        if (step + 1 < nsteps) {
+#pragma unroll
+          for (int i = 0; i < CI; ++i)
+            if (FULL || i < Cu) xv[i][sl] = ubase[i * Npts + (n2 + 2) * NT];
+        }
+        asm volatile("" ::: "memory");
+      }
+      // lane 4b+j now holds channel 4T+j at the four t of its quad
+      float* op = out + (b * Co + j4) * Npts + poff;
+      if (ep.zsave != nullptr) {
+        float* zp = ep.zsave + (b * Co + j4) * Npts + poff;
+#pragma unroll
+        for (int T = 0; T < CT; ++T)
+          if (FULL || 4 * T + j4 < Co)
+            *reinterpret_cast<float4*>(zp + (4 * T) * Npts) = make_float4(acc[T][0], acc[T][1], acc[T][2], acc[T][3]);
+      }
+      if (ep.act) {
+#pragma unroll
+        for (int T = 0; T < CT; ++T)
+          if (FULL || 4 * T + j4 < Co)
+            *reinterpret_cast<float4*>(op + (4 * T) * Npts) =
+                make_float4(gelu_fast_f(acc[T][0]), gelu_fast_f(acc[T][1]), gelu_fast_f(acc[T][2]),
+                            gelu_fast_f(acc[T][3]));
+      } else {
+#pragma unroll
+        for (int T = 0; T < CT; ++T)
+          if (FULL || 4 * T + j4 < Co)
+            *reinterpret_cast<float4*>(op + (4 * T) * Npts) = make_float4(acc[T][0], acc[T][1], acc[T][2], acc[T][3]);
       }
     }
   }
@@ -1363,7 +1559,7 @@ int zt_mfma_region(AxisPlan az, int mt, int Co, int q) {
 
 int zt_mfma_blob(AxisPlan az, int Nt, int mt, int Co, int Cu, int q) {
   const int CP = 4 * ((Co + 3) / 4 <= 2 ? 2 : ((Co + 3) / 4 <= 5 ? 5 : 8));
-  return ((2 * mt * Nt + Cu * CP + 2 * q * az.L + 255) / 256) * 256;      // whole 1 KiB wave loads
+  return ((2 * mt * Nt + Cu * CP + 2 * q * az.L + CP + 255) / 256) * 256;      // whole 1 KiB wave loads
 }
 
 size_t zt_mfma_lds(AxisPlan az, int Nt, int mt, int Co, int Cu, int q) {
@@ -1384,6 +1580,32 @@ hipError_t launch_zt_inv(const float2* a, float* out, const float2* twt, const f
   const bool aligned = ((reinterpret_cast<uintptr_t>(out) | reinterpret_cast<uintptr_t>(ep.u) |
                          reinterpret_cast<uintptr_t>(ep.zsave) | reinterpret_cast<uintptr_t>(a) |
                          reinterpret_cast<uintptr_t>(tables)) & 15) == 0;
+  // Column kernel (Nt = 32, 16-point z FFT): the spectrum of a column is staged once instead of
+  // once per tile.  Taken when two blocks fit a CU's LDS, else the per-tile kernel below.
+  if (aligned && tables != nullptr && Nt == 32 && az.M == 16 && az.P >= 2 && az.P % 2 == 0 &&
+      (az.P & (az.P - 1)) == 0 && CT <= 5 && Co * mt <= 512 && (az.L * mt) % 2 == 0 && B <= 65535) {
+    const int Cu = ep.u ? ep.Cu : 0;
+    const int a_stride4 = zt_mfma_astride4(az, mt);
+    const int a_floats = (Co * a_stride4 * 4 + 255) & ~255;
+    const int v_stride = zt_mfma_vstride(az, mt, 1);
+    const int blob_floats = zt_mfma_blob(az, Nt, mt, Co, Cu, az.P);
+    const size_t lds = ((size_t)a_floats + 2 * 4 * CT * v_stride + blob_floats) * 4;
+    if (Cu <= 4 * CT && lds <= (size_t)(79 * 1024) && (size_t)blob_floats * 4 <= kZtTablesBytes) {
+      const bool full = (Co == 4 * CT) && (ep.u == nullptr || ep.Cu == 4 * CT);
+      const int inv_mt = (65536 + mt - 1) / mt;
+      hipLaunchKernelGGL(zt_tables_kernel, dim3(1), dim3(256), 0, s, tables, twt, twz, ep.u ? ep.W : nullptr,
+                         ep.w_so, ep.w_si, ep.bias, Co, Cu, 4 * CT, mt, Nt, az.L, az.P, az.P, blob_floats);
+      const dim3 grid((unsigned)NxNy, (unsigned)B);
+#define FNO_ZTC(CTV, FULLV)                                                                        \
+  hipLaunchKernelGGL((zt_inv_col_kernel<CTV, FULLV>), grid, dim3(512), lds, s, a, out, Co, NxNy,   \
+                     az.N, az.L, az.npos, mt, inv_mt, a_floats, a_stride4, v_stride, tables,       \
+                     blob_floats, e)
+      if (CT == 2) { if (full) FNO_ZTC(2, true); else FNO_ZTC(2, false); }
+      else { if (full) FNO_ZTC(5, true); else FNO_ZTC(5, false); }
+#undef FNO_ZTC
+      return hipGetLastError();
+    }
+  }
   if (qf > 0 && aligned) {
     const int G = az.P / qf;
     const int64_t gx = (int64_t)((NxNy + 7) / 8) * 8 * G;
@@ -1396,7 +1618,7 @@ hipError_t launch_zt_inv(const float2* a, float* out, const float2* twt, const f
     const int blob_floats = zt_mfma_blob(az, Nt, mt, Co, ep.u ? ep.Cu : 0, qf);
     if (tables == nullptr || (size_t)G * blob_floats * 4 > kZtTablesBytes) return hipErrorInvalidValue;
     hipLaunchKernelGGL(zt_tables_kernel, dim3(G), dim3(256), 0, s, tables, twt, twz, ep.u ? ep.W : nullptr,
-                       ep.w_so, ep.w_si, Co, ep.u ? ep.Cu : 0, 4 * CT, mt, Nt, az.L, az.P, qf, blob_floats);
+                       ep.w_so, ep.w_si, ep.bias, Co, ep.u ? ep.Cu : 0, 4 * CT, mt, Nt, az.L, az.P, qf, blob_floats);
 #define FNO_ZTM(NTV, MZV, CTV, FULLV, NWV)                                                          \
   hipLaunchKernelGGL((zt_inv_mfma_kernel<NTV, MZV, CTV, FULLV, NWV>), grid, dim3(thr), lds, s, a,   \
                      out, twt, twz, Co, NxNy, az.N, az.L, az.npos, mt, ilog2(qf), ilog2(G), inv_mt, \
