@@ -80,6 +80,9 @@ SMALL = [
     (2, 2, 3, (3, 2, 32, 16), (1, 1, 6, 9), 0),        # same, two residue classes per block, Cin != Cout
     (1, 20, 20, (2, 2, 32, 32), (1, 1, 8, 9), 0),      # same, width 20, Nt = 32
     (1, 24, 24, (2, 2, 32, 16), (1, 1, 4, 4), 0),      # same, width 24 (eight channel tiles)
+    (1, 8, 8, (2, 3, 128, 32), (1, 1, 16, 9), 0),      # column kernel (Nt = 32): four steps per column
+    (2, 3, 5, (3, 2, 64, 32), (1, 1, 6, 5), 0),        # same, padded channel tiles, Cin != Cout
+    (1, 4, 4, (2, 2, 32, 32), (1, 1, 16, 17), 0),      # same, one step, every z and t mode kept
 ]
 
 
