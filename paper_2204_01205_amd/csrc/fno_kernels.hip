@@ -977,16 +977,38 @@ __global__ __launch_bounds__(512, 4) void zt_inv_col_kernel(
       // z stage: item (o, kt) collects the kept z-frequencies with their twiddles into MZ bins;
       // an inverse FFT over n1 gives the rows z = Pz n1 + n2
       if (tid < nitems) {
+        // The kept frequency k_j goes to bin k_j mod MZ.  When Lz is a multiple of MZ that is
+        // j mod MZ for the stored order j as well (k_j = j or j - Lz), every bin gets Lz / MZ
+        // terms, and a round of MZ consecutive j needs no index arithmetic: its reads go out
+        // together.  Other Lz take one term at a time.
         const float2* twq = TW + n2 * Lz;
         float2 gres[MZ];
 #pragma unroll
-        for (int m = 0; m < MZ; ++m) {
-          float2 accb = make_float2(0.f, 0.f);
-          for (int k = kmin + ((m + mbase) & (MZ - 1)); k <= kmax; k += MZ) {
-            const int j = k >= 0 ? k : k + Lz;
-            accb = cfmac(asrc[j * mt], twq[j], accb);
+        for (int m = 0; m < MZ; ++m) gres[m] = make_float2(0.f, 0.f);
+        if ((Lz & (MZ - 1)) == 0) {
+          for (int r0 = 0; r0 < Lz; r0 += MZ) {
+            const float2* ar = asrc + r0 * mt;
+            const float2* tr = twq + r0;
+#pragma unroll
+            for (int mb = 0; mb < MZ; mb += 8) {
+              float2 av[8], wv8[8];
+#pragma unroll
+              for (int u = 0; u < 8; ++u) {
+                av[u] = ar[(mb + u) * mt];
+                wv8[u] = tr[mb + u];
+              }
+#pragma unroll
+              for (int u = 0; u < 8; ++u) gres[mb + u] = cfmac(av[u], wv8[u], gres[mb + u]);
+            }
           }
-          gres[m] = accb;
+        } else {
+#pragma unroll
+          for (int m = 0; m < MZ; ++m) {
+            for (int k = kmin + ((m + mbase) & (MZ - 1)); k <= kmax; k += MZ) {
+              const int j = k >= 0 ? k : k + Lz;
+              gres[m] = cfmac(asrc[j * mt], twq[j], gres[m]);
+            }
+          }
         }
         fft_reg<MZ, +1>(gres);
 #pragma unroll
