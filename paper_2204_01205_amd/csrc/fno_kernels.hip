@@ -199,6 +199,28 @@ __device__ __forceinline__ void rfft_row_bins(const float4 (&quads)[NT / 4], int
 // t stage spread over all banks; a wave's load still covers whole 128-byte lines.  The t-stage
 // results wait in registers over a barrier so the complex tile T can reuse the LDS of S.
 // Pz is a power of two and inv_mt = ceil(2^16 / mt) (shifts and a multiply instead of divisions).
+// sum_i w[i] * x[i * xs] over n terms, eight at a time so that their reads are issued together
+// (a term-by-term loop waits for every read before the next one goes out)
+__device__ __forceinline__ float2 combine_terms(const float2* w, const float2* x, int xs, int n) {
+  float2 acc0 = make_float2(0.f, 0.f), acc1 = make_float2(0.f, 0.f);
+  int i = 0;
+  for (; i + 8 <= n; i += 8) {
+    float2 wv[8], xv[8];
+#pragma unroll
+    for (int u = 0; u < 8; ++u) {
+      wv[u] = w[i + u];
+      xv[u] = x[(i + u) * xs];
+    }
+#pragma unroll
+    for (int u = 0; u < 8; u += 2) {
+      acc0 = cfma(wv[u], xv[u], acc0);
+      acc1 = cfma(wv[u + 1], xv[u + 1], acc1);
+    }
+  }
+  for (; i < n; ++i) acc0 = cfma(w[i], x[i * xs], acc0);
+  return make_float2(acc0.x + acc1.x, acc0.y + acc1.y);
+}
+
 template <int NT, int MZ>
 __global__ __launch_bounds__(kThreads) void tz_fwd_fast_kernel(
     const float* __restrict__ x, float2* __restrict__ out, const float2* __restrict__ twz,
@@ -327,9 +349,7 @@ __global__ __launch_bounds__(kThreads) void axis_fwd_kernel(
       const int mj = posmod(kfreq(j, L, npos), M);
       const float2* base = F + (P * mj) * W + col;
       const float2* w = (tw_lds ? TWs : tw) + j * P;
-      float2 acc = make_float2(0.f, 0.f);
-      for (int n2 = 0; n2 < P; ++n2) acc = cfma(w[n2], base[n2 * W], acc);
-      out[(o * L + j) * inner + c0 + col] = acc;
+      out[(o * L + j) * inner + c0 + col] = combine_terms(w, base, W, P);
     }
   }
 }
