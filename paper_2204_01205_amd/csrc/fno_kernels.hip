@@ -1044,7 +1044,27 @@ __global__ __launch_bounds__(512, 4) void zt_inv_col_kernel(
       }
       const float* cs_lane = CS + 4 * quad + j4;
       const float2* v0 = V + j4 * v_stride + n1 * mt;
-      for (int kt = 0; kt < mt; ++kt) {
+      int kt = 0;
+      constexpr int KB = 3;                       // kt per pass: their reads go out together
+      for (; kt + KB <= mt; kt += KB) {
+        float cs4[2 * KB];
+        float2 va[KB][CT];
+#pragma unroll
+        for (int h = 0; h < KB; ++h) {
+          cs4[2 * h] = cs_lane[(2 * (kt + h)) * NT];
+          cs4[2 * h + 1] = cs_lane[(2 * (kt + h) + 1) * NT];
+#pragma unroll
+          for (int T = 0; T < CT; ++T) va[h][T] = v0[4 * T * v_stride + kt + h];
+        }
+#pragma unroll
+        for (int h = 0; h < KB; ++h)
+#pragma unroll
+          for (int T = 0; T < CT; ++T) {
+            acc[T] = __builtin_amdgcn_mfma_f32_4x4x1f32(cs4[2 * h], va[h][T].x, acc[T], 0, 0, 0);
+            acc[T] = __builtin_amdgcn_mfma_f32_4x4x1f32(cs4[2 * h + 1], va[h][T].y, acc[T], 0, 0, 0);
+          }
+      }
+      for (; kt < mt; ++kt) {
         const float c = cs_lane[(2 * kt) * NT];
         const float sn = cs_lane[(2 * kt + 1) * NT];
         float2 va[CT];
