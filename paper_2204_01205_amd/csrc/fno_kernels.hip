@@ -1481,7 +1481,7 @@ hipError_t launch_tz_fwd(const float* x, float2* out, const float2* twt, const f
                     tz_fast_lds(az, Nt, mt, 1) <= (size_t)kLdsBudget;
   if (fast) {
     int ppb = 1;
-    while (ppb * 2 * az.N <= 128 && tz_fast_lds(az, Nt, mt, ppb * 2) <= (size_t)kLdsBudget) ppb *= 2;
+    while (ppb * 2 * az.N <= 256 && tz_fast_lds(az, Nt, mt, ppb * 2) <= (size_t)kLdsBudget) ppb *= 2;
     const int thr = ((ppb * az.N + 63) / 64) * 64;
     const size_t lds = tz_fast_lds(az, Nt, mt, ppb);
     const int region = tz_fast_region(az, Nt, mt, ppb);
