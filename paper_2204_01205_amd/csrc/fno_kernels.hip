@@ -1384,10 +1384,11 @@ __global__ __launch_bounds__(kThreads) void pointwise_mlp2_kernel(
 }
 
 int pick_q(AxisPlan az, int Nt) {
-  // smallest divisor Q of Pz whose Q adjacent rows span at least 128 bytes
+  // smallest divisor Q of Pz whose Q adjacent rows span at least 128 bytes; a single row when
+  // that divisor would make the tile taller than 64 rows (Pz prime or nearly so)
   for (int q = 1; q <= az.P; ++q)
-    if (az.P % q == 0 && q * Nt >= 32) return q;
-  return az.P;
+    if (az.P % q == 0 && q * Nt >= 32) return q * az.M <= 64 ? q : 1;
+  return 1;
 }
 
 size_t tz_fwd_lds(AxisPlan az, int Nt, int mt, int ppb) {

@@ -24,6 +24,10 @@ CONFIGS = {
                  in_channels=5, hidden=128, blocks=4),
     "cfg4": dict(batch=1, width=20, grid=(256, 256, 128, 32), modes=(24, 24, 16, 9), op="block_fwd"),
     "cfg5": dict(batch=4, width=20, grid=(128, 128, 128, 16), modes=(16, 16, 16, 9), op="block_fwd_bwd"),
+    # the grid shapes of the paper's own workloads (Sec. 4: training samples and the full Sleipner
+    # model); the mode counts are not stated there and are chosen here
+    "sleipner_train": dict(batch=1, width=20, grid=(60, 60, 64, 30), modes=(12, 12, 12, 8), op="block_fwd"),
+    "sleipner_full": dict(batch=1, width=20, grid=(68, 118, 263, 16), modes=(12, 16, 24, 8), op="block_fwd"),
 }
 
 

@@ -91,6 +91,13 @@ def test_cfg4_block_forward_full_size_sampled():
     check_block_forward("cfg4")
 
 
+@pytest.mark.parametrize("name", ["sleipner_train", "sleipner_full"])
+def test_paper_grid_shapes_block_forward_full_size_sampled(name):
+    """The grid shapes of the paper's own workloads (Sec. 4): 60 x 60 x 64 x 30 and 68 x 118 x 263 x 16,
+    none of them on the power-of-two fast paths (mixed radix, Nt = 30, a prime length 263)."""
+    check_block_forward(name)
+
+
 def test_cfg3_block_forward_and_pointwise_full_size_sampled():
     v = check_block_forward("cfg3")
     grid, pts = v["grid"], v["pts"]
