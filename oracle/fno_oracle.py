@@ -412,6 +412,20 @@ def pointwise_linear(x, w, b=None):
     return channel_affine(x, w, b)
 
 
+def time_lift(a, wt, bt, wc, bc):
+    """The two input lifts of Sec. 2.4 (eqs. (8)-(9)), applied one after the other as written.
+
+    a (B, Cin, Nx, Ny, Nz, 1): input with a time axis of length one.
+    a_1 = W_t a + b_t along the time axis (W_t: (nt, 1), b_t: (nt,)) gives (B, Cin, Nx, Ny, Nz, nt);
+    nu  = W_c a_1 + b_c along the channel axis (W_c: (C, Cin), b_c: (C,)) gives (B, C, ..., nt).
+    """
+    a = np.asarray(a, np.float64)
+    wt = np.asarray(wt, np.float64).reshape(-1, 1)
+    bt = np.asarray(bt, np.float64).reshape(-1)
+    a1 = np.tensordot(a, wt, axes=([5], [1])) + bt              # contraction over the unit time axis
+    return channel_affine(a1, wc, bc)
+
+
 def pointwise_mlp2(x, w1, b1, w2, b2):
     """Projection to the output channels through one hidden layer: W2 sigma(W1 x + b1) + b2."""
     return channel_affine(gelu(channel_affine(x, w1, b1)), w2, b2)

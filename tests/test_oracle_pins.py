@@ -447,3 +447,40 @@ def test_oracle_reproduces_its_frozen_fixture():
     assert set(got) == set(stored)
     for name, v in got.items():
         assert abs(float(v) - stored[name]) <= 1e-12 * max(1.0, abs(stored[name])), name
+
+
+def test_time_lift_against_loops_closed_forms_and_the_channel_lift():
+    """Sec. 2.4, eqs. (8)-(9): a_1 = W_t a + b_t along time, nu = W_c a_1 + b_c along channels."""
+    rng = np.random.default_rng(31)
+    B, Cin, C, grid, nt = 2, 3, 4, (2, 3, 2), 5
+    a = rng.standard_normal((B, Cin) + grid + (1,))
+    wt, bt = rng.standard_normal(nt), rng.standard_normal(nt)
+    wc, bc = rng.standard_normal((C, Cin)), rng.standard_normal(C)
+    got = O.time_lift(a, wt, bt, wc, bc)
+    assert got.shape == (B, C) + grid + (nt,)
+    # plain loops over every index
+    want = np.zeros_like(got)
+    for b in range(B):
+        for c in range(C):
+            for x in range(grid[0]):
+                for y in range(grid[1]):
+                    for z in range(grid[2]):
+                        for t in range(nt):
+                            acc = bc[c]
+                            for j in range(Cin):
+                                acc += wc[c, j] * (wt[t] * a[b, j, x, y, z, 0] + bt[t])
+                            want[b, c, x, y, z, t] = acc
+    assert np.max(np.abs(got - want)) <= 1e-13
+    # zero input: nu[c, t] = b_t[t] * sum_j W_c[c, j] + b_c[c] at every point
+    zero = O.time_lift(np.zeros_like(a), wt, bt, wc, bc)
+    closed = bt[None, :] * wc.sum(axis=1)[:, None] + bc[:, None]
+    assert np.max(np.abs(zero - closed[None, :, None, None, None, :])) <= 1e-13
+    # W_t = 1, b_t = 0: every time slice is the channel lift of the input
+    ones = O.time_lift(a, np.ones(nt), np.zeros(nt), wc, bc)
+    lifted = O.pointwise_linear(a, wc, bc)
+    assert np.max(np.abs(ones - np.repeat(lifted, nt, axis=5))) <= 1e-13
+    # affine in a: differences are linear and lose both biases
+    a2 = rng.standard_normal(a.shape)
+    d = O.time_lift(a + a2, wt, bt, wc, bc) - O.time_lift(a2, wt, bt, wc, bc)
+    lin = O.time_lift(a, wt, np.zeros(nt), wc, np.zeros(C))
+    assert np.max(np.abs(d - lin)) <= 1e-12
