@@ -127,6 +127,16 @@ int fno_block_bwd(const fno_desc* desc, const float* x, const float* R, const fl
 int fno_pointwise_linear(int32_t batch, int32_t c_in, int32_t c_out, int64_t npoints,
                          const float* x, const float* W, const float* bias, float* y, void* stream);
 
+/* Input lifts of Sec. 2.4 (eqs. (8)-(9)), fused: the input a [B][c_in][nspace] has a time axis of
+ * length one; a_1 = Wt a + bt along time (Wt, bt: nt values each), then the channel lift
+ * nu = Wc a_1 + bc (Wc [c_out][c_in], bc [c_out]) gives out [B][c_out][nspace][nt], t contiguous.
+ * All pointers are device pointers owned by the caller; bt and bc nullable; out 16-byte aligned
+ * when nt is a multiple of 4; c_out <= 32.  Asynchronous on `stream`; nothing is launched on an
+ * argument error. */
+int fno_time_lift(int32_t batch, int32_t c_in, int32_t c_out, int64_t nspace, int32_t nt, const float* a,
+                  const float* Wt, const float* bt, const float* Wc, const float* bc, float* out,
+                  void* stream);
+
 /* Projection to the output channels (end of Sec. 2.4) through one hidden layer, fused per point:
  *   y = W2 gelu(W1 x + b1) + b2,  W1 [hidden][c_in], W2 [c_out][hidden].  The hidden tensor is
  * never stored.  c_in <= 32, c_out <= 4. */

@@ -23,7 +23,7 @@ FNO_FLAG_MSE_TARGET = 1
 
 EXPORTS = [
     "fno_workspace_bytes", "fno_mode_indices", "fno_spectral_conv_fwd", "fno_spectral_conv_bwd",
-    "fno_block_fwd", "fno_block_bwd", "fno_pointwise_linear", "fno_pointwise_mlp2",
+    "fno_block_fwd", "fno_block_bwd", "fno_pointwise_linear", "fno_pointwise_mlp2", "fno_time_lift",
     "fno_status_string", "fno_timing_enable", "fno_timing_read",
 ]
 
@@ -156,6 +156,13 @@ def fno_pointwise_linear(batch, c_in, c_out, npoints, x, W, bias, y) -> None:
     _check(lib().fno_pointwise_linear(ctypes.c_int32(batch), ctypes.c_int32(c_in), ctypes.c_int32(c_out),
                                       ctypes.c_int64(npoints), _ptr(x, name="x"), _ptr(W, name="W"),
                                       _ptr(bias, name="bias"), _ptr(y, name="y"), _stream()))
+
+
+def fno_time_lift(batch, c_in, c_out, nspace, nt, a, Wt, bt, Wc, bc, out) -> None:
+    _check(lib().fno_time_lift(ctypes.c_int32(batch), ctypes.c_int32(c_in), ctypes.c_int32(c_out),
+                               ctypes.c_int64(nspace), ctypes.c_int32(nt), _ptr(a, name="a"),
+                               _ptr(Wt, name="Wt"), _ptr(bt, name="bt"), _ptr(Wc, name="Wc"),
+                               _ptr(bc, name="bc"), _ptr(out, name="out"), _stream()))
 
 
 def fno_pointwise_mlp2(batch, c_in, hidden, c_out, npoints, x, W1, b1, W2, b2, y) -> None:

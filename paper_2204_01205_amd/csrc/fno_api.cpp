@@ -374,6 +374,18 @@ int fno_pointwise_mlp2(int32_t batch, int32_t c_in, int32_t hidden, int32_t c_ou
   return FNO_OK;
 }
 
+int fno_time_lift(int32_t batch, int32_t c_in, int32_t c_out, int64_t nspace, int32_t nt, const float* a,
+                  const float* Wt, const float* bt, const float* Wc, const float* bc, float* out,
+                  void* stream) {
+  if (batch < 1 || c_in < 1 || c_out < 1 || nspace < 0 || nt < 1) { set_detail("sizes must be positive"); return FNO_EINVAL; }
+  if (a == nullptr || Wt == nullptr || Wc == nullptr || out == nullptr) { set_detail("a, Wt, Wc and out are required"); return FNO_EINVAL; }
+  if (c_out > 32 || batch > 65535) { set_detail("time_lift covers c_out <= 32, batch <= 65535"); return FNO_EUNSUPPORTED; }
+  if (nt % 4 == 0 && misaligned16(out)) { set_detail("out must be 16-byte aligned"); return FNO_EINVAL; }
+  FNO_HIP(fno::launch_time_lift(batch, c_in, c_out, nspace, nt, a, Wt, bt, Wc, bc, out,
+                                static_cast<hipStream_t>(stream)));
+  return FNO_OK;
+}
+
 int fno_timing_enable(int on) {
   g_timing_on = on != 0;
   g_timing_used = 0;

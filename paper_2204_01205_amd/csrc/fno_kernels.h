@@ -71,6 +71,10 @@ hipError_t launch_pointwise_mlp2(int B, int Ci, int H, int Co, int64_t np, const
                                  const float* W1, const float* b1, const float* W2,
                                  const float* b2, float* y, hipStream_t s);
 
+// Input lifts: a [B][Ci][np] (time axis of length one) -> out [B][Co][np][Nt].
+hipError_t launch_time_lift(int B, int Ci, int Co, int64_t np, int Nt, const float* a, const float* wt,
+                            const float* bt, const float* wc, const float* bc, float* out, hipStream_t s);
+
 // Limits of the kernels (checked by the API before any launch).
 constexpr int kMaxFftM = 32;        // largest in-register FFT
 constexpr int kMaxCo = 32;          // accumulator file of the epilogue

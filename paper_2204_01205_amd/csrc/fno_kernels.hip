@@ -1354,6 +1354,63 @@ __global__ __launch_bounds__(kThreads) void pointwise_linear_kernel(
     if (o < Co) y[(b * Co + o) * np + p] = acc[o];
 }
 
+// Input lifts of Sec. 2.4 (eqs. (8)-(9)) in one sweep: a_1 = W_t a + b_t along a time axis of
+// length one, then nu = W_c a_1 + b_c along the channels, i.e.
+//   nu[b][c][p][t] = W_t[t] s_c(p) + b_t[t] r_c + b_c[c],  s_c(p) = sum_j W_c[c][j] a[b][j][p],
+//   r_c = sum_j W_c[c][j].
+// One thread: one spatial point and four consecutive t; the output (the only large tensor) is
+// written once, a is read through the cache by the threads that share a point.
+template <int CO>
+__global__ __launch_bounds__(kThreads) void time_lift_kernel(
+    int Ci, int Co, long long np, int Nt, const float* __restrict__ a, const float* __restrict__ wt,
+    const float* __restrict__ bt, const float* __restrict__ wc, const float* __restrict__ bc,
+    float* __restrict__ out) {
+  const int nt4 = (Nt + 3) >> 2;
+  const long long e = (long long)blockIdx.x * kThreads + threadIdx.x;
+  const long long b = blockIdx.y;
+  if (e >= np * nt4) return;
+  const long long p = e / nt4;
+  const int t0 = 4 * (int)(e - p * nt4);
+  float sc[CO], rc[CO];
+#pragma unroll
+  for (int c = 0; c < CO; ++c) { sc[c] = 0.f; rc[c] = 0.f; }
+  for (int j = 0; j < Ci; ++j) {
+    const float av = a[(b * Ci + j) * np + p];
+#pragma unroll
+    for (int c = 0; c < CO; ++c) {
+      if (c < Co) {
+        const float w = wc[c * Ci + j];
+        sc[c] = fmaf(w, av, sc[c]);
+        rc[c] += w;
+      }
+    }
+  }
+  float w4[4], b4[4];
+#pragma unroll
+  for (int u = 0; u < 4; ++u) {
+    w4[u] = t0 + u < Nt ? wt[t0 + u] : 0.f;
+    b4[u] = (bt != nullptr && t0 + u < Nt) ? bt[t0 + u] : 0.f;
+  }
+  const bool vec = (Nt & 3) == 0;      // rows of whole float4s (the base pointer is checked on the host)
+#pragma unroll
+  for (int c = 0; c < CO; ++c) {
+    if (c < Co) {
+      const float bias = bc != nullptr ? bc[c] : 0.f;
+      float v[4];
+#pragma unroll
+      for (int u = 0; u < 4; ++u) v[u] = fmaf(w4[u], sc[c], fmaf(b4[u], rc[c], bias));
+      float* dst = out + ((b * Co + c) * np + p) * Nt + t0;
+      if (vec) {
+        *reinterpret_cast<float4*>(dst) = make_float4(v[0], v[1], v[2], v[3]);
+      } else {
+#pragma unroll
+        for (int u = 0; u < 4; ++u)
+          if (t0 + u < Nt) dst[u] = v[u];
+      }
+    }
+  }
+}
+
 template <int CI>
 __global__ __launch_bounds__(kThreads) void pointwise_mlp2_kernel(
     int Ci, int H, int Co, long long np, const float* __restrict__ x, const float* __restrict__ W1,
@@ -1806,6 +1863,27 @@ hipError_t launch_pointwise_mlp2(int B, int Ci, int H, int Co, int64_t np, const
   else
     hipLaunchKernelGGL((pointwise_mlp2_kernel<32>), grid, dim3(kThreads), 0, s, Ci, H, Co,
                        (long long)np, x, W1, b1, W2, b2, y);
+  return hipGetLastError();
+}
+
+hipError_t launch_time_lift(int B, int Ci, int Co, int64_t np, int Nt, const float* a, const float* wt,
+                            const float* bt, const float* wc, const float* bc, float* out, hipStream_t s) {
+  const int nt4 = (Nt + 3) / 4;
+  const int64_t nb = (np * nt4 + kThreads - 1) / kThreads;
+  if (nb > 0x7fffffffLL || B > 65535 || Co > 32) return hipErrorInvalidValue;
+  if (nb == 0 || B == 0) return hipSuccess;
+  // float4 stores need whole quads per row and an aligned tensor
+  if ((Nt & 3) == 0 && (reinterpret_cast<uintptr_t>(out) & 15) != 0) return hipErrorInvalidValue;
+  dim3 grid((unsigned)nb, (unsigned)B);
+  if (Co <= 8)
+    hipLaunchKernelGGL((time_lift_kernel<8>), grid, dim3(kThreads), 0, s, Ci, Co, (long long)np, Nt, a, wt,
+                       bt, wc, bc, out);
+  else if (Co <= 20)
+    hipLaunchKernelGGL((time_lift_kernel<20>), grid, dim3(kThreads), 0, s, Ci, Co, (long long)np, Nt, a, wt,
+                       bt, wc, bc, out);
+  else
+    hipLaunchKernelGGL((time_lift_kernel<32>), grid, dim3(kThreads), 0, s, Ci, Co, (long long)np, Nt, a, wt,
+                       bt, wc, bc, out);
   return hipGetLastError();
 }
 

@@ -295,3 +295,29 @@ def test_block_against_the_stored_oracle_fixture():
         close(gb[o], f"gb[{o}]", np.abs(gb).max())
         for i in range(3):
             close(gW[o, i], f"gW[{o}][{i}]", np.abs(gW).max())
+
+
+@pytest.mark.parametrize("shape", [
+    # batch, c_in, c_out, spatial grid, nt
+    (2, 2, 20, (6, 5, 4), 30),        # the paper's two input channels, nt not a multiple of 4
+    (1, 3, 8, (4, 4, 8), 16),         # whole float4 rows
+    (1, 1, 24, (3, 2, 5), 7),         # odd nt, one input channel, width above 20
+    (1, 2, 20, (60, 60, 64), 30),     # a training sample of the paper (Sec. 4), full size
+])
+def test_time_lift_matches_oracle(shape):
+    batch, c_in, c_out, grid, nt = shape
+    rng = np.random.default_rng([7, batch, c_in, c_out, nt])
+    a = rng.standard_normal((batch, c_in) + grid + (1,)).astype(np.float32)
+    wt = rng.standard_normal(nt).astype(np.float32)
+    bt = rng.standard_normal(nt).astype(np.float32)
+    wc = (rng.standard_normal((c_out, c_in)) / np.sqrt(c_in)).astype(np.float32)
+    bc = (0.1 * rng.standard_normal(c_out)).astype(np.float32)
+    nspace = int(np.prod(grid))
+    out = torch.empty((batch, c_out) + grid + (nt,), device="cuda")
+    B.fno_time_lift(batch, c_in, c_out, nspace, nt, dev(a), dev(wt), dev(bt), dev(wc), dev(bc), out)
+    torch.cuda.synchronize()
+    assert rel(host(out), O.time_lift(a, wt, bt, wc, bc)) <= TOL
+    # without the biases
+    B.fno_time_lift(batch, c_in, c_out, nspace, nt, dev(a), dev(wt), None, dev(wc), None, out)
+    torch.cuda.synchronize()
+    assert rel(host(out), O.time_lift(a, wt, np.zeros(nt), wc, np.zeros(c_out))) <= TOL
