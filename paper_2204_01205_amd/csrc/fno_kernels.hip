@@ -520,7 +520,7 @@ __global__ __launch_bounds__(kThreads) void zt_inv_kernel(
     int Q, EpiArgs ep) {
   HIP_DYNAMIC_SHARED(float, smem)
   const int Pz = Nz / MZ;
-  const int G = Pz / Q;
+  const int G = (Pz + Q - 1) / Q;             // the last group of residue classes may be ragged
   const int Rz = Q * MZ;
   const int sY = Nt + 1;
   float2* V = reinterpret_cast<float2*>(smem);                 // [Co][Rz][mt]
@@ -538,12 +538,27 @@ __global__ __launch_bounds__(kThreads) void zt_inv_kernel(
     const int kt = (idx / Q) % mt;
     const int o = idx / (Q * mt);
     const int n2 = g * Q + q;
+    if (n2 >= Pz) continue;
     const float2* src = a + (((b * Co + o) * NxNy + xy) * Lz) * mt + kt;
     float2 gbin[MZ];
 #pragma unroll
     for (int m = 0; m < MZ; ++m) {
       float2 acc = make_float2(0.f, 0.f);
-      for (int k = kmin + posmod(m - kmin, MZ); k <= kmax; k += MZ) {
+      int k = kmin + posmod(m - kmin, MZ);
+      // four terms at a time: their loads (global memory, served by L2) go out together
+      for (; k + 3 * MZ <= kmax; k += 4 * MZ) {
+        float2 av[4], wv[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+          const int kk = k + u * MZ;
+          const int j = kk >= 0 ? kk : kk + Lz;
+          av[u] = src[j * mt];
+          wv[u] = twz[j * Pz + n2];
+        }
+#pragma unroll
+        for (int u = 0; u < 4; ++u) acc = cfmac(av[u], wv[u], acc);
+      }
+      for (; k <= kmax; k += MZ) {
         const int j = k >= 0 ? k : k + Lz;
         acc = cfmac(src[j * mt], twz[j * Pz + n2], acc);
       }
@@ -583,6 +598,7 @@ __global__ __launch_bounds__(kThreads) void zt_inv_kernel(
   const long long Npts = (long long)NxNy * Nz * Nt;
   for (int idx = tid; idx < Rz * Nt; idx += kThreads) {
     const int t = idx % Nt, r = idx / Nt;
+    if (g * Q + (r % Q) >= Pz) continue;
     const int z = Pz * (r / Q) + g * Q + (r % Q);
     const long long off = (xy * Nz + z) * Nt + t;
     float acc[CO];
@@ -1441,11 +1457,17 @@ __global__ __launch_bounds__(kThreads) void pointwise_mlp2_kernel(
 }
 
 int pick_q(AxisPlan az, int Nt) {
-  // smallest divisor Q of Pz whose Q adjacent rows span at least 128 bytes; a single row when
-  // that divisor would make the tile taller than 64 rows (Pz prime or nearly so)
+  // smallest divisor Q of Pz whose Q adjacent rows span at least 128 bytes; when that would make
+  // the tile taller than 64 rows (Pz prime or nearly so): a Q that
+  // need not divide Pz (the kernel skips the classes past the end of the last group), sized
+  // for about one grid point per thread
   for (int q = 1; q <= az.P; ++q)
-    if (az.P % q == 0 && q * Nt >= 32) return q * az.M <= 64 ? q : 1;
-  return 1;
+    if (az.P % q == 0 && q * Nt >= 32 && q * az.M <= 64) return q;
+  int q = 256 / (Nt * az.M);        // about one point per thread
+  if (q < 1) q = 1;
+  if (q > az.P) q = az.P;
+  while (q > 1 && q * az.M > 64) --q;
+  return q;
 }
 
 size_t tz_fwd_lds(AxisPlan az, int Nt, int mt, int ppb) {
@@ -1770,7 +1792,7 @@ hipError_t launch_zt_inv(const float2* a, float* out, const float2* twt, const f
     return hipGetLastError();
   }
   const int Q = pick_q(az, Nt);
-  const int G = az.P / Q;
+  const int G = (az.P + Q - 1) / Q;
   const int64_t nblk = ncols * G;
   if (nblk > 0x7fffffffLL) return hipErrorInvalidValue;
   const size_t lds = zt_inv_lds(az, Nt, mt, Co);
