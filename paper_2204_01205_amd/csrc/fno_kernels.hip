@@ -648,15 +648,16 @@ typedef float v4f __attribute__((ext_vector_type(4)));
 __global__ void zt_tables_kernel(float* __restrict__ blob, const float2* __restrict__ twt,
                                  const float2* __restrict__ twz, const float* __restrict__ W, int w_so,
                                  int w_si, const float* __restrict__ bias, int Co, int Cu, int CP, int mt,
-                                 int NT, int Lz, int Pz, int Q, int blob_floats) {
+                                 int NT, int nt_act, int Lz, int Pz, int Q, int blob_floats) {
   const int g = blockIdx.x;
   float* dst = blob + (long long)g * blob_floats;
   const int n_cs = 2 * mt * NT, n_wt = (W != nullptr) ? Cu * CP : 0, n_tw = 2 * Q * Lz;
   for (int idx = threadIdx.x; idx < blob_floats; idx += blockDim.x) {
     float v = 0.f;
     if (idx < n_cs) {
+      // rows padded from the axis length nt_act to the tile width NT with zeros
       const int k = idx / NT, t = idx - k * NT;
-      const float2 w = twt[(k >> 1) * NT + t];
+      const float2 w = t < nt_act ? twt[(k >> 1) * nt_act + t] : make_float2(0.f, 0.f);
       v = (k & 1) ? w.y : w.x;
     } else if (idx < n_cs + n_wt) {
       const int e = idx - n_cs;
@@ -678,10 +679,26 @@ __global__ void zt_tables_kernel(float* __restrict__ blob, const float2* __restr
 // Launch: grid (8 * G * ceil(NxNy / 8), B), 64 NW threads (a tile of NW * 128 / NT rows).  Q and G are powers of two (shifts
 // instead of divisions); inv_mt = ceil(2^16 / mt) turns the division by mt into a multiply.
 // FULL means Co == 4 CT and (no linear term or Cu == 4 CT): channel guards vanish at compile time.
-template <int NT, int MZ, int CT, bool FULL, int NW>
+// Four consecutive t of one channel: one 16-byte store, or, for a row length that is only even,
+// the pairs of the quad that exist.
+template <bool TPAD>
+__device__ __forceinline__ void store_quad(float* dst, int valid, float4 v) {
+  if constexpr (!TPAD) {
+    *reinterpret_cast<float4*>(dst) = v;
+  } else {
+    if (valid >= 2) *reinterpret_cast<float2*>(dst) = make_float2(v.x, v.y);
+    if (valid >= 4) *reinterpret_cast<float2*>(dst + 2) = make_float2(v.z, v.w);
+  }
+}
+
+// TPAD: the t axis is shorter than the tile (nt_act < NT, nt_act even): rows of nt_act floats in
+// memory, the tile's last quads partly or wholly outside (their u values read as zero, their
+// table columns are zero, their results are not stored; stores go as float2 pairs, which the
+// even row length keeps 8-byte aligned).
+template <int NT, int MZ, int CT, bool FULL, int NW, bool TPAD>
 __global__ __launch_bounds__(64 * NW, NW == 8 ? 4 : (CT >= 8 ? 2 : 3)) void zt_inv_mfma_kernel(
     const float2* __restrict__ a, float* __restrict__ out, const float2* __restrict__ twt,
-    const float2* __restrict__ twz, int Co_rt, int NxNy, int Nz, int Lz, int nposz, int mt,
+    const float2* __restrict__ twz, int Co_rt, int NxNy, int Nz, int nt_act, int Lz, int nposz, int mt,
     int qshift, int gshift, int inv_mt, int region_floats, int a_stride4, int v_stride, const float* __restrict__ blob, int blob_floats, EpiArgs ep) {
   HIP_DYNAMIC_SHARED(float, smem)
   constexpr int CP = 4 * CT;                 // channels padded to whole MFMA tiles
@@ -720,9 +737,11 @@ __global__ __launch_bounds__(64 * NW, NW == 8 ? 4 : (CT >= 8 ? 2 : 3)) void zt_i
   for (int sl = 0; sl < 2; ++sl) {
     rowt[sl] = wave * RPW + (sl * 16 + blk) / QPR;
     const int z = Pz * (rowt[sl] >> qshift) + (g << qshift) + (rowt[sl] & (Q - 1));
-    poff[sl] = ((long long)xy * Nz + z) * NT + 4 * quad;
+    poff[sl] = ((long long)xy * Nz + z) * (TPAD ? nt_act : NT) + 4 * quad;
   }
-  const long long Npts = (long long)NxNy * Nz * NT;
+  const long long Npts = (long long)NxNy * Nz * (TPAD ? nt_act : NT);
+  const bool t_in = !TPAD || 4 * quad + j4 < nt_act;        // this lane's t of the quad exists
+  const int quad_valid = TPAD ? nt_act - 4 * quad : 4;       // points of the quad that exist (<= 0, 2 or >= 4)
   const int kmin = nposz - Lz, kmax = nposz - 1;
   const int mbase = posmod(-kmin, MZ);
   const int nitems = (Co * mt) << qshift;
@@ -760,8 +779,8 @@ __global__ __launch_bounds__(64 * NW, NW == 8 ? 4 : (CT >= 8 ? 2 : 3)) void zt_i
 #pragma unroll
     for (int i = 0; i < CI; ++i) {
       if (FULL || i < Cu) {
-        xv[i][0] = up[i * Npts + poff[0]];
-        xv[i][1] = up[i * Npts + poff[1]];
+        xv[i][0] = t_in ? up[i * Npts + poff[0]] : 0.f;
+        xv[i][1] = t_in ? up[i * Npts + poff[1]] : 0.f;
       }
     }
   }
@@ -884,8 +903,8 @@ __global__ __launch_bounds__(64 * NW, NW == 8 ? 4 : (CT >= 8 ? 2 : 3)) void zt_i
       if (FULL || 4 * T + j4 < Co) {
 #pragma unroll
         for (int sl = 0; sl < 2; ++sl)
-          *reinterpret_cast<float4*>(zp + (4 * T) * Npts + poff[sl]) =
-              make_float4(acc[T][sl][0], acc[T][sl][1], acc[T][sl][2], acc[T][sl][3]);
+          store_quad<TPAD>(zp + (4 * T) * Npts + poff[sl], quad_valid,
+                           make_float4(acc[T][sl][0], acc[T][sl][1], acc[T][sl][2], acc[T][sl][3]));
       }
     }
   }
@@ -895,9 +914,9 @@ __global__ __launch_bounds__(64 * NW, NW == 8 ? 4 : (CT >= 8 ? 2 : 3)) void zt_i
       if (FULL || 4 * T + j4 < Co) {
 #pragma unroll
         for (int sl = 0; sl < 2; ++sl)
-          *reinterpret_cast<float4*>(op + (4 * T) * Npts + poff[sl]) =
-              make_float4(gelu_fast_f(acc[T][sl][0]), gelu_fast_f(acc[T][sl][1]),
-                          gelu_fast_f(acc[T][sl][2]), gelu_fast_f(acc[T][sl][3]));
+          store_quad<TPAD>(op + (4 * T) * Npts + poff[sl], quad_valid,
+                           make_float4(gelu_fast_f(acc[T][sl][0]), gelu_fast_f(acc[T][sl][1]),
+                                       gelu_fast_f(acc[T][sl][2]), gelu_fast_f(acc[T][sl][3])));
       }
     }
   } else {
@@ -906,8 +925,8 @@ __global__ __launch_bounds__(64 * NW, NW == 8 ? 4 : (CT >= 8 ? 2 : 3)) void zt_i
       if (FULL || 4 * T + j4 < Co) {
 #pragma unroll
         for (int sl = 0; sl < 2; ++sl)
-          *reinterpret_cast<float4*>(op + (4 * T) * Npts + poff[sl]) =
-              make_float4(acc[T][sl][0], acc[T][sl][1], acc[T][sl][2], acc[T][sl][3]);
+          store_quad<TPAD>(op + (4 * T) * Npts + poff[sl], quad_valid,
+                           make_float4(acc[T][sl][0], acc[T][sl][1], acc[T][sl][2], acc[T][sl][3]));
       }
     }
   }
@@ -1523,7 +1542,11 @@ bool mfma_cfg_ok(AxisPlan az, int Nt, int mt, int Co, int Cu, int nw, size_t lds
   return q > 0 && (az.L * mt) % 2 == 0 && Co * mt * q <= (nw == 8 ? 512 : 512) && Co <= kMaxCo && Cu <= 4 * CT &&
          (nw == 4 || CT <= 5) && zt_mfma_lds(az, Nt, mt, Co, Cu, q) <= lds_cap;
 }
-bool zt_mfma_fits(AxisPlan az, int Nt, int mt, int Co, int Cu) { return mfma_nw(az, Nt, mt, Co, Cu) > 0; }
+int mfma_tile_nt(int Nt);
+bool zt_mfma_fits(AxisPlan az, int Nt, int mt, int Co, int Cu) {
+  const int ntt = mfma_tile_nt(Nt);
+  return ntt > 0 && mfma_nw(az, ntt, mt, Co, Cu) > 0;
+}
 
 hipError_t launch_axis_table(float2* tw, AxisPlan ax, hipStream_t s) {
   const int n = ax.L * ax.P;
@@ -1648,6 +1671,14 @@ hipError_t launch_mix_bwd(const float2* xh, const float2* R, const float2* gh, f
 // Tile of the matrix-core kernel: Q residue classes whose Rz = Q*M rows times Nt points make
 // 128..512 points (64..256 threads, two points each) and whose Q adjacent rows span at least 128 bytes.
 // Rows per tile for NW waves: each wave covers 128 points.  Returns Q = rows / M, or 0.
+// t-tile of the matrix-core kernels for an axis of length Nt: 16 or 32 points, the axis itself or
+// the next tile width above an even length; 0 when neither fits
+int mfma_tile_nt(int Nt) {
+  if (Nt == 16 || Nt == 32) return Nt;
+  if (Nt % 2 != 0 || Nt < 10 || Nt > 32) return 0;
+  return Nt < 16 ? 16 : 32;
+}
+
 int mfma_q_nw(AxisPlan az, int Nt, int nw) {
   if (Nt != 16 && Nt != 32) return 0;
   if (az.M != 8 && az.M != 16) return 0;
@@ -1717,8 +1748,10 @@ hipError_t launch_zt_inv(const float2* a, float* out, const float2* twt, const f
   EpiArgs e{ep.u, ep.Cu, ep.W, ep.w_so, ep.w_si, ep.bias, ep.zsave, ep.act};
   const int NxNy = Nx * Ny;
   const int CT = (Co + 3) / 4 <= 2 ? 2 : ((Co + 3) / 4 <= 5 ? 5 : 8);
-  const int nw = mfma_nw(az, Nt, mt, Co, ep.u ? ep.Cu : 0);
-  const int qf = nw > 0 ? mfma_q_nw(az, Nt, nw) : 0;
+  const int ntt = mfma_tile_nt(Nt);           // t-tile of the matrix-core kernels (0: none)
+  const bool tpad = ntt != Nt;
+  const int nw = ntt > 0 ? mfma_nw(az, ntt, mt, Co, ep.u ? ep.Cu : 0) : 0;
+  const int qf = nw > 0 ? mfma_q_nw(az, ntt, nw) : 0;
   const bool aligned = ((reinterpret_cast<uintptr_t>(out) | reinterpret_cast<uintptr_t>(ep.u) |
                          reinterpret_cast<uintptr_t>(ep.zsave) | reinterpret_cast<uintptr_t>(a) |
                          reinterpret_cast<uintptr_t>(tables)) & 15) == 0;
@@ -1736,7 +1769,7 @@ hipError_t launch_zt_inv(const float2* a, float* out, const float2* twt, const f
       const bool full = (Co == 4 * CT) && (ep.u == nullptr || ep.Cu == 4 * CT);
       const int inv_mt = (65536 + mt - 1) / mt;
       hipLaunchKernelGGL(zt_tables_kernel, dim3(1), dim3(256), 0, s, tables, twt, twz, ep.u ? ep.W : nullptr,
-                         ep.w_so, ep.w_si, ep.bias, Co, Cu, 4 * CT, mt, Nt, az.L, az.P, az.P, blob_floats);
+                         ep.w_so, ep.w_si, ep.bias, Co, Cu, 4 * CT, mt, Nt, Nt, az.L, az.P, az.P, blob_floats);
       const dim3 grid((unsigned)NxNy, (unsigned)B);
 #define FNO_ZTC(CTV, FULLV)                                                                        \
   hipLaunchKernelGGL((zt_inv_col_kernel<CTV, FULLV>), grid, dim3(512), lds, s, a, out, Co, NxNy,   \
@@ -1753,38 +1786,42 @@ hipError_t launch_zt_inv(const float2* a, float* out, const float2* twt, const f
     const int64_t gx = (int64_t)((NxNy + 7) / 8) * 8 * G;
     if (gx > 0x7fffffffLL || B > 65535 || Co * mt > 7000) return hipErrorInvalidValue;
     const int thr = 64 * nw;
-    const size_t lds = zt_mfma_lds(az, Nt, mt, Co, ep.u ? ep.Cu : 0, qf);
+    const size_t lds = zt_mfma_lds(az, ntt, mt, Co, ep.u ? ep.Cu : 0, qf);
     const int inv_mt = (65536 + mt - 1) / mt;
-    const bool full = (Co == 4 * CT) && (ep.u == nullptr || ep.Cu == 4 * CT);
+    const bool full = !tpad && (Co == 4 * CT) && (ep.u == nullptr || ep.Cu == 4 * CT);
     const dim3 grid((unsigned)gx, (unsigned)B);
-    const int blob_floats = zt_mfma_blob(az, Nt, mt, Co, ep.u ? ep.Cu : 0, qf);
+    const int blob_floats = zt_mfma_blob(az, ntt, mt, Co, ep.u ? ep.Cu : 0, qf);
     if (tables == nullptr || (size_t)G * blob_floats * 4 > kZtTablesBytes) return hipErrorInvalidValue;
     hipLaunchKernelGGL(zt_tables_kernel, dim3(G), dim3(256), 0, s, tables, twt, twz, ep.u ? ep.W : nullptr,
-                       ep.w_so, ep.w_si, ep.bias, Co, ep.u ? ep.Cu : 0, 4 * CT, mt, Nt, az.L, az.P, qf, blob_floats);
-#define FNO_ZTM(NTV, MZV, CTV, FULLV, NWV)                                                          \
-  hipLaunchKernelGGL((zt_inv_mfma_kernel<NTV, MZV, CTV, FULLV, NWV>), grid, dim3(thr), lds, s, a,   \
-                     out, twt, twz, Co, NxNy, az.N, az.L, az.npos, mt, ilog2(qf), ilog2(G), inv_mt, \
-                     zt_mfma_region(az, mt, Co, qf), zt_mfma_astride4(az, mt), zt_mfma_vstride(az, mt, qf),  \
-                     tables, blob_floats, e)
-#define FNO_ZTM_F(NTV, MZV, CTV)                                  \
-  do {                                                            \
-    if (nw == 8 && full) FNO_ZTM(NTV, MZV, CTV, true, 8);         \
-    else if (nw == 8) FNO_ZTM(NTV, MZV, CTV, false, 8);           \
-    else if (full) FNO_ZTM(NTV, MZV, CTV, true, 4);               \
-    else FNO_ZTM(NTV, MZV, CTV, false, 4);                        \
+                       ep.w_so, ep.w_si, ep.bias, Co, ep.u ? ep.Cu : 0, 4 * CT, mt, ntt, Nt, az.L, az.P, qf,
+                       blob_floats);
+#define FNO_ZTM(NTV, MZV, CTV, FULLV, NWV, TPADV)                                                     \
+  hipLaunchKernelGGL((zt_inv_mfma_kernel<NTV, MZV, CTV, FULLV, NWV, TPADV>), grid, dim3(thr), lds, s, \
+                     a, out, twt, twz, Co, NxNy, az.N, Nt, az.L, az.npos, mt, ilog2(qf), ilog2(G),    \
+                     inv_mt, zt_mfma_region(az, mt, Co, qf), zt_mfma_astride4(az, mt),                \
+                     zt_mfma_vstride(az, mt, qf), tables, blob_floats, e)
+#define FNO_ZTM_F(NTV, MZV, CTV)                                         \
+  do {                                                                   \
+    if (tpad && nw == 8) FNO_ZTM(NTV, MZV, CTV, false, 8, true);         \
+    else if (tpad) FNO_ZTM(NTV, MZV, CTV, false, 4, true);               \
+    else if (nw == 8 && full) FNO_ZTM(NTV, MZV, CTV, true, 8, false);    \
+    else if (nw == 8) FNO_ZTM(NTV, MZV, CTV, false, 8, false);           \
+    else if (full) FNO_ZTM(NTV, MZV, CTV, true, 4, false);               \
+    else FNO_ZTM(NTV, MZV, CTV, false, 4, false);                        \
   } while (0)
-#define FNO_ZTM_CT(NTV, MZV)                            \
-  do {                                                  \
-    if (CT == 2) FNO_ZTM_F(NTV, MZV, 2);                \
-    else if (CT == 5) FNO_ZTM_F(NTV, MZV, 5);           \
-    else FNO_ZTM(NTV, MZV, 8, false, 4);                \
+#define FNO_ZTM_CT(NTV, MZV)                                        \
+  do {                                                              \
+    if (CT == 2) FNO_ZTM_F(NTV, MZV, 2);                            \
+    else if (CT == 5) FNO_ZTM_F(NTV, MZV, 5);                       \
+    else if (tpad) FNO_ZTM(NTV, MZV, 8, false, 4, true);            \
+    else FNO_ZTM(NTV, MZV, 8, false, 4, false);                     \
   } while (0)
 #define FNO_ZTM_M(NTV)                                  \
   do {                                                  \
     if (az.M == 8) FNO_ZTM_CT(NTV, 8);                  \
     else FNO_ZTM_CT(NTV, 16);                           \
   } while (0)
-    if (Nt == 16) FNO_ZTM_M(16); else FNO_ZTM_M(32);
+    if (ntt == 16) FNO_ZTM_M(16); else FNO_ZTM_M(32);
 #undef FNO_ZTM_M
 #undef FNO_ZTM_CT
 #undef FNO_ZTM_F

@@ -83,6 +83,9 @@ SMALL = [
     (1, 8, 8, (2, 3, 128, 32), (1, 1, 16, 9), 0),      # column kernel (Nt = 32): four steps per column
     (2, 3, 5, (3, 2, 64, 32), (1, 1, 6, 5), 0),        # same, padded channel tiles, Cin != Cout
     (1, 4, 4, (2, 2, 32, 32), (1, 1, 16, 17), 0),      # same, one step, every z and t mode kept
+    (1, 8, 8, (3, 2, 32, 30), (1, 1, 4, 8), 0),        # matrix-core inverse kernel, t axis padded 30 -> 32
+    (2, 3, 3, (2, 3, 32, 12), (1, 1, 6, 4), 0),        # same, 12 -> 16, padded channel tiles
+    (1, 20, 20, (2, 2, 64, 30), (1, 1, 12, 8), 0),     # same, width 20, the z and t lengths of the paper's samples
 ]
 
 
