@@ -74,6 +74,28 @@ __global__ void t_table_kernel(float2* tw, int Nt, int mt) {
 // ------------------------------------------------------------------------------------------
 // Forward (t, z): one block transforms `ppb` contiguous (b,c,nx,ny) planes of Nz x Nt reals
 // ------------------------------------------------------------------------------------------
+// sum_i w[i] * x[i * xs] over n terms, eight at a time so that their reads are issued together
+// (a term-by-term loop waits for every read before the next one goes out)
+__device__ __forceinline__ float2 combine_terms(const float2* w, const float2* x, int xs, int n) {
+  float2 acc0 = make_float2(0.f, 0.f), acc1 = make_float2(0.f, 0.f);
+  int i = 0;
+  for (; i + 8 <= n; i += 8) {
+    float2 wv[8], xv[8];
+#pragma unroll
+    for (int u = 0; u < 8; ++u) {
+      wv[u] = w[i + u];
+      xv[u] = x[(i + u) * xs];
+    }
+#pragma unroll
+    for (int u = 0; u < 8; u += 2) {
+      acc0 = cfma(wv[u], xv[u], acc0);
+      acc1 = cfma(wv[u + 1], xv[u + 1], acc1);
+    }
+  }
+  for (; i < n; ++i) acc0 = cfma(w[i], x[i * xs], acc0);
+  return make_float2(acc0.x + acc1.x, acc0.y + acc1.y);
+}
+
 template <int MZ>
 __global__ __launch_bounds__(kThreads) void tz_fwd_kernel(
     const float* __restrict__ x, float2* __restrict__ out, const float2* __restrict__ twt,
@@ -108,7 +130,26 @@ __global__ __launch_bounds__(kThreads) void tz_fwd_kernel(
       float2 acc[4];
 #pragma unroll
       for (int u = 0; u < 4; ++u) acc[u] = make_float2(0.f, 0.f);
-      for (int n = 0; n < Nt; ++n) {
+      int n = 0;
+      for (; n + 4 <= Nt; n += 4) {         // four points per pass: their reads go out together
+        float v[4];
+#pragma unroll
+        for (int h = 0; h < 4; ++h) v[h] = srow[n + h];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+          if (kt0 + u < mt) {
+            float2 w[4];
+#pragma unroll
+            for (int h = 0; h < 4; ++h) w[h] = twt[(kt0 + u) * Nt + n + h];
+#pragma unroll
+            for (int h = 0; h < 4; ++h) {
+              acc[u].x = fmaf(v[h], w[h].x, acc[u].x);
+              acc[u].y = fmaf(v[h], w[h].y, acc[u].y);
+            }
+          }
+        }
+      }
+      for (; n < Nt; ++n) {
         const float v = srow[n];
 #pragma unroll
         for (int u = 0; u < 4; ++u) {
@@ -149,9 +190,7 @@ __global__ __launch_bounds__(kThreads) void tz_fwd_kernel(
     const int mj = posmod(kfreq(jz, Lz, nposz), MZ);
     const float2* base = T + (p * mt + kt) * sT + Pz * mj;
     const float2* w = twz + jz * Pz;
-    float2 acc = make_float2(0.f, 0.f);
-    for (int n2 = 0; n2 < Pz; ++n2) acc = cfma(w[n2], base[n2], acc);
-    out[((plane0 + p) * Lz + jz) * mt + kt] = acc;
+    out[((plane0 + p) * Lz + jz) * mt + kt] = combine_terms(w, base, 1, Pz);
   }
 }
 
@@ -199,28 +238,6 @@ __device__ __forceinline__ void rfft_row_bins(const float4 (&quads)[NT / 4], int
 // t stage spread over all banks; a wave's load still covers whole 128-byte lines.  The t-stage
 // results wait in registers over a barrier so the complex tile T can reuse the LDS of S.
 // Pz is a power of two and inv_mt = ceil(2^16 / mt) (shifts and a multiply instead of divisions).
-// sum_i w[i] * x[i * xs] over n terms, eight at a time so that their reads are issued together
-// (a term-by-term loop waits for every read before the next one goes out)
-__device__ __forceinline__ float2 combine_terms(const float2* w, const float2* x, int xs, int n) {
-  float2 acc0 = make_float2(0.f, 0.f), acc1 = make_float2(0.f, 0.f);
-  int i = 0;
-  for (; i + 8 <= n; i += 8) {
-    float2 wv[8], xv[8];
-#pragma unroll
-    for (int u = 0; u < 8; ++u) {
-      wv[u] = w[i + u];
-      xv[u] = x[(i + u) * xs];
-    }
-#pragma unroll
-    for (int u = 0; u < 8; u += 2) {
-      acc0 = cfma(wv[u], xv[u], acc0);
-      acc1 = cfma(wv[u + 1], xv[u + 1], acc1);
-    }
-  }
-  for (; i < n; ++i) acc0 = cfma(w[i], x[i * xs], acc0);
-  return make_float2(acc0.x + acc1.x, acc0.y + acc1.y);
-}
-
 template <int NT, int MZ>
 __global__ __launch_bounds__(kThreads) void tz_fwd_fast_kernel(
     const float* __restrict__ x, float2* __restrict__ out, const float2* __restrict__ twz,
