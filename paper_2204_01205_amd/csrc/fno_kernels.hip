@@ -562,18 +562,20 @@ __global__ __launch_bounds__(kThreads) void zt_inv_kernel(
     for (int m = 0; m < MZ; ++m) {
       float2 acc = make_float2(0.f, 0.f);
       int k = kmin + posmod(m - kmin, MZ);
-      // four terms at a time: their loads (global memory, served by L2) go out together
-      for (; k + 3 * MZ <= kmax; k += 4 * MZ) {
-        float2 av[4], wv[4];
+      // several terms at a time: their loads (global memory, served by L2) go out together;
+      // more of them where the bins leave the registers free (dense or nearly dense z)
+      constexpr int UB = MZ <= 2 ? 16 : 4;
+      for (; k + (UB - 1) * MZ <= kmax; k += UB * MZ) {
+        float2 av[UB], wv[UB];
 #pragma unroll
-        for (int u = 0; u < 4; ++u) {
+        for (int u = 0; u < UB; ++u) {
           const int kk = k + u * MZ;
           const int j = kk >= 0 ? kk : kk + Lz;
           av[u] = src[j * mt];
           wv[u] = twz[j * Pz + n2];
         }
 #pragma unroll
-        for (int u = 0; u < 4; ++u) acc = cfmac(av[u], wv[u], acc);
+        for (int u = 0; u < UB; ++u) acc = cfmac(av[u], wv[u], acc);
       }
       for (; k <= kmax; k += MZ) {
         const int j = k >= 0 ? k : k + Lz;
@@ -622,8 +624,20 @@ __global__ __launch_bounds__(kThreads) void zt_inv_kernel(
 #pragma unroll
     for (int o = 0; o < CO; ++o) acc[o] = (ep.bias != nullptr && o < Co) ? ep.bias[o] : 0.f;
     if (ep.u != nullptr) {
-      for (int i = 0; i < ep.Cu; ++i) {
-        const float xv = ep.u[(b * ep.Cu + i) * Npts + off];
+      const float* up = ep.u + (b * ep.Cu) * Npts + off;
+      int i = 0;
+      for (; i + 4 <= ep.Cu; i += 4) {         // four input channels per pass: their loads go out together
+        float xv[4];
+#pragma unroll
+        for (int h = 0; h < 4; ++h) xv[h] = up[(i + h) * Npts];
+#pragma unroll
+        for (int h = 0; h < 4; ++h)
+#pragma unroll
+          for (int o = 0; o < CO; ++o)
+            if (o < Co) acc[o] = fmaf(ep.W[o * ep.w_so + (i + h) * ep.w_si], xv[h], acc[o]);
+      }
+      for (; i < ep.Cu; ++i) {
+        const float xv = up[i * Npts];
 #pragma unroll
         for (int o = 0; o < CO; ++o)
           if (o < Co) acc[o] = fmaf(ep.W[o * ep.w_so + i * ep.w_si], xv, acc[o]);
