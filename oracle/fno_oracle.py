@@ -426,6 +426,37 @@ def time_lift(a, wt, bt, wc, bc):
     return channel_affine(a1, wc, bc)
 
 
+def rel_l2_loss(pred, target):
+    """Relative L2 misfit of Sec. 4: ||pred - target||_2 / ||target||_2 over all entries."""
+    pred = np.asarray(pred, np.float64)
+    target = np.asarray(target, np.float64)
+    return float(np.sqrt(np.sum((pred - target) ** 2)) / np.sqrt(np.sum(target ** 2)))
+
+
+def rel_l2_grad(pred, target):
+    """d(rel_l2_loss)/d(pred) = (pred - target) / (||pred - target||_2 ||target||_2); zero where pred == target everywhere."""
+    pred = np.asarray(pred, np.float64)
+    target = np.asarray(target, np.float64)
+    d = pred - target
+    nd = np.sqrt(np.sum(d ** 2))
+    if nd == 0.0:
+        return np.zeros_like(d)
+    return d / (nd * np.sqrt(np.sum(target ** 2)))
+
+
+def adam_step(param, grad, m, v, step, lr=1e-3, beta1=0.9, beta2=0.999, eps=1e-8):
+    """One update of Adam (Kingma & Ba, Algorithm 1; the optimiser of Sec. 4, learning rate 1e-3).
+
+    step counts from 1.  Complex parameters are updated as pairs of reals.  Returns (param, m, v).
+    """
+    param, grad = np.asarray(param, np.float64), np.asarray(grad, np.float64)
+    m = beta1 * np.asarray(m, np.float64) + (1.0 - beta1) * grad
+    v = beta2 * np.asarray(v, np.float64) + (1.0 - beta2) * grad * grad
+    mhat = m / (1.0 - beta1 ** step)
+    vhat = v / (1.0 - beta2 ** step)
+    return param - lr * mhat / (np.sqrt(vhat) + eps), m, v
+
+
 def pointwise_mlp2(x, w1, b1, w2, b2):
     """Projection to the output channels through one hidden layer: W2 sigma(W1 x + b1) + b2."""
     return channel_affine(gelu(channel_affine(x, w1, b1)), w2, b2)

@@ -484,3 +484,61 @@ def test_time_lift_against_loops_closed_forms_and_the_channel_lift():
     d = O.time_lift(a + a2, wt, bt, wc, bc) - O.time_lift(a2, wt, bt, wc, bc)
     lin = O.time_lift(a, wt, np.zeros(nt), wc, np.zeros(C))
     assert np.max(np.abs(d - lin)) <= 1e-12
+
+
+def test_relative_l2_loss_and_its_gradient():
+    """Sec. 4: L(y, yhat) = ||y - yhat||_2 / ||yhat||_2."""
+    # a 3-4-5 example by hand: difference (3, 4, 0), target (0, 0, 10) -> 5 / 10
+    target = np.array([0.0, 0.0, 10.0])
+    pred = target + np.array([3.0, 4.0, 0.0])
+    assert abs(O.rel_l2_loss(pred, target) - 0.5) <= 1e-15
+    g = O.rel_l2_grad(pred, target)
+    assert np.max(np.abs(g - np.array([3.0, 4.0, 0.0]) / 50.0)) <= 1e-16
+    rng = np.random.default_rng(5)
+    y = rng.standard_normal((2, 1, 3, 4, 2, 3))
+    u = rng.standard_normal(y.shape)
+    # pred = (1 + alpha) target gives |alpha|; a common positive factor cancels
+    assert abs(O.rel_l2_loss(1.25 * y, y) - 0.25) <= 1e-14
+    assert abs(O.rel_l2_loss(3.0 * u, 3.0 * y) - O.rel_l2_loss(u, y)) <= 1e-14
+    # against plain loops
+    sd = sum((a - b) ** 2 for a, b in zip(u.ravel(), y.ravel()))
+    sy = sum(b * b for b in y.ravel())
+    assert abs(O.rel_l2_loss(u, y) - math.sqrt(sd) / math.sqrt(sy)) <= 1e-14
+    # the gradient: central differences, and <grad, pred - target> = loss (degree-one homogeneity)
+    g = O.rel_l2_grad(u, y)
+    for idx in [(0, 0, 0, 0, 0, 0), (1, 0, 2, 3, 1, 2), (0, 0, 1, 2, 0, 1)]:
+        e = np.zeros_like(u)
+        e[idx] = 1e-6
+        fd = (O.rel_l2_loss(u + e, y) - O.rel_l2_loss(u - e, y)) / 2e-6
+        assert abs(fd - g[idx]) <= 1e-9
+    assert abs(np.sum(g * (u - y)) - O.rel_l2_loss(u, y)) <= 1e-14
+    assert np.all(O.rel_l2_grad(y, y) == 0.0)
+
+
+def test_adam_step_against_closed_forms():
+    """Kingma & Ba, Algorithm 1 (Sec. 4 trains with Adam, learning rate 1e-3)."""
+    rng = np.random.default_rng(9)
+    p0 = rng.standard_normal(50)
+    g = rng.standard_normal(50)
+    zeros = np.zeros(50)
+    # first step from zero moments: mhat = g, vhat = g^2, the step is lr * g / (|g| + eps)
+    p1, m1, v1 = O.adam_step(p0, g, zeros, zeros, 1, lr=1e-3, beta1=0.9, beta2=0.999, eps=1e-8)
+    assert np.max(np.abs(m1 - 0.1 * g)) <= 1e-16 and np.max(np.abs(v1 - 0.001 * g * g)) <= 1e-16
+    assert np.max(np.abs(p1 - (p0 - 1e-3 * g / (np.abs(g) + 1e-8)))) <= 1e-15
+    # a constant gradient keeps mhat = g and vhat = g^2 at every step
+    p, m, v = p0, zeros, zeros
+    for t in range(1, 8):
+        p, m, v = O.adam_step(p, g, m, v, t)
+    assert np.max(np.abs(p - (p0 - 7 * 1e-3 * g / (np.abs(g) + 1e-8)))) <= 1e-14
+    # zero gradient: the moments decay, the parameter moves by lr * mhat / (sqrt(vhat) + eps)
+    p2, m2, v2 = O.adam_step(p1, zeros, m1, v1, 2)
+    assert np.max(np.abs(m2 - 0.9 * m1)) <= 1e-17 and np.max(np.abs(v2 - 0.999 * v1)) <= 1e-18
+    mhat, vhat = m2 / (1 - 0.9 ** 2), v2 / (1 - 0.999 ** 2)
+    assert np.max(np.abs(p2 - (p1 - 1e-3 * mhat / (np.sqrt(vhat) + 1e-8)))) <= 1e-15
+    # element by element with scalar arithmetic
+    q, mq, vq = O.adam_step(p0, g, m1, v1, 3, lr=2e-3, beta1=0.8, beta2=0.99, eps=1e-6)
+    for i in (0, 17, 49):
+        mi = 0.8 * m1[i] + 0.2 * g[i]
+        vi = 0.99 * v1[i] + 0.01 * g[i] ** 2
+        want = p0[i] - 2e-3 * (mi / (1 - 0.8 ** 3)) / (math.sqrt(vi / (1 - 0.99 ** 3)) + 1e-6)
+        assert abs(q[i] - want) <= 1e-14 and abs(mq[i] - mi) <= 1e-15 and abs(vq[i] - vi) <= 1e-15
