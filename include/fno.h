@@ -137,6 +137,26 @@ int fno_time_lift(int32_t batch, int32_t c_in, int32_t c_out, int64_t nspace, in
                   const float* Wt, const float* bt, const float* Wc, const float* bc, float* out,
                   void* stream);
 
+/* Relative L2 misfit of Sec. 4 over n floats:  loss = ||pred - target||_2 / ||target||_2, written to
+ * the device scalar `loss` (nullable), and its gradient with respect to pred,
+ * (pred - target) / (||pred - target||_2 ||target||_2), written to grad (nullable, n floats; all
+ * zero when pred equals target).  The sums are accumulated in double in a fixed order: the same
+ * bits on every run.  ws: device scratch of fno_rel_l2_workspace_bytes() bytes, 8-byte aligned,
+ * owned by the caller.  A zero target gives the IEEE result of the division.  Asynchronous on
+ * `stream`; nothing is launched on an argument error. */
+int fno_rel_l2_workspace_bytes(size_t* bytes);
+int fno_rel_l2_loss(int64_t n, const float* pred, const float* target, float* loss, float* grad,
+                    void* ws, size_t ws_bytes, void* stream);
+
+/* One step of Adam (the optimiser of Sec. 4; Kingma & Ba, Algorithm 1) in place on n floats:
+ *   m = beta1 m + (1 - beta1) g;  v = beta2 v + (1 - beta2) g^2;
+ *   param -= lr (m / (1 - beta1^step)) / (sqrt(v / (1 - beta2^step)) + eps).
+ * step counts from 1.  Complex parameters (the spectral weights) are passed as 2n floats: real
+ * and imaginary parts are updated as separate reals.  All pointers are device pointers owned by
+ * the caller. */
+int fno_adam_step(int64_t n, float* param, const float* grad, float* m, float* v, double lr, double beta1,
+                  double beta2, double eps, int32_t step, void* stream);
+
 /* Projection to the output channels (end of Sec. 2.4) through one hidden layer, fused per point:
  *   y = W2 gelu(W1 x + b1) + b2,  W1 [hidden][c_in], W2 [c_out][hidden].  The hidden tensor is
  * never stored.  c_in <= 32, c_out <= 4. */

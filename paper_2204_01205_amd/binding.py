@@ -24,6 +24,7 @@ FNO_FLAG_MSE_TARGET = 1
 EXPORTS = [
     "fno_workspace_bytes", "fno_mode_indices", "fno_spectral_conv_fwd", "fno_spectral_conv_bwd",
     "fno_block_fwd", "fno_block_bwd", "fno_pointwise_linear", "fno_pointwise_mlp2", "fno_time_lift",
+    "fno_rel_l2_workspace_bytes", "fno_rel_l2_loss", "fno_adam_step",
     "fno_status_string", "fno_timing_enable", "fno_timing_read",
 ]
 
@@ -163,6 +164,24 @@ def fno_time_lift(batch, c_in, c_out, nspace, nt, a, Wt, bt, Wc, bc, out) -> Non
                                ctypes.c_int64(nspace), ctypes.c_int32(nt), _ptr(a, name="a"),
                                _ptr(Wt, name="Wt"), _ptr(bt, name="bt"), _ptr(Wc, name="Wc"),
                                _ptr(bc, name="bc"), _ptr(out, name="out"), _stream()))
+
+
+def fno_rel_l2_workspace_bytes() -> int:
+    n = ctypes.c_size_t(0)
+    _check(lib().fno_rel_l2_workspace_bytes(ctypes.byref(n)))
+    return int(n.value)
+
+
+def fno_rel_l2_loss(n, pred, target, loss, grad, ws) -> None:
+    _check(lib().fno_rel_l2_loss(ctypes.c_int64(n), _ptr(pred, name="pred"), _ptr(target, name="target"),
+                                 _ptr(loss, name="loss"), _ptr(grad, name="grad"), _ptr(ws, name="ws"),
+                                 ctypes.c_size_t(ws.numel() * ws.element_size()), _stream()))
+
+
+def fno_adam_step(n, param, grad, m, v, lr, beta1, beta2, eps, step) -> None:
+    _check(lib().fno_adam_step(ctypes.c_int64(n), _ptr(param, name="param"), _ptr(grad, name="grad"),
+                               _ptr(m, name="m"), _ptr(v, name="v"), ctypes.c_double(lr), ctypes.c_double(beta1),
+                               ctypes.c_double(beta2), ctypes.c_double(eps), ctypes.c_int32(step), _stream()))
 
 
 def fno_pointwise_mlp2(batch, c_in, hidden, c_out, npoints, x, W1, b1, W2, b2, y) -> None:

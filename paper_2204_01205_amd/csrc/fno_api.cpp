@@ -386,6 +386,33 @@ int fno_time_lift(int32_t batch, int32_t c_in, int32_t c_out, int64_t nspace, in
   return FNO_OK;
 }
 
+int fno_rel_l2_workspace_bytes(size_t* bytes) {
+  if (bytes == nullptr) { set_detail("bytes is required"); return FNO_EINVAL; }
+  *bytes = fno::rel_l2_workspace_bytes();
+  return FNO_OK;
+}
+
+int fno_rel_l2_loss(int64_t n, const float* pred, const float* target, float* loss, float* grad,
+                    void* ws, size_t ws_bytes, void* stream) {
+  if (n < 1) { set_detail("n must be positive"); return FNO_EINVAL; }
+  if (pred == nullptr || target == nullptr || ws == nullptr) { set_detail("pred, target and ws are required"); return FNO_EINVAL; }
+  if (loss == nullptr && grad == nullptr) { set_detail("one of loss and grad is required"); return FNO_EINVAL; }
+  if (ws_bytes < fno::rel_l2_workspace_bytes()) { set_detail("workspace too small"); return FNO_ENOSPC; }
+  if (reinterpret_cast<uintptr_t>(ws) % 8 != 0) { set_detail("ws must be 8-byte aligned"); return FNO_EINVAL; }
+  FNO_HIP(fno::launch_rel_l2(n, pred, target, loss, grad, static_cast<double*>(ws),
+                             static_cast<hipStream_t>(stream)));
+  return FNO_OK;
+}
+
+int fno_adam_step(int64_t n, float* param, const float* grad, float* m, float* v, double lr, double beta1,
+                  double beta2, double eps, int32_t step, void* stream) {
+  if (n < 0 || step < 1) { set_detail("n must be non-negative and step at least 1"); return FNO_EINVAL; }
+  if (n > 0 && (param == nullptr || grad == nullptr || m == nullptr || v == nullptr)) { set_detail("param, grad, m and v are required"); return FNO_EINVAL; }
+  if (!(beta1 >= 0.0 && beta1 < 1.0 && beta2 >= 0.0 && beta2 < 1.0)) { set_detail("beta1 and beta2 must lie in [0, 1)"); return FNO_EINVAL; }
+  FNO_HIP(fno::launch_adam(n, param, grad, m, v, lr, beta1, beta2, eps, step, static_cast<hipStream_t>(stream)));
+  return FNO_OK;
+}
+
 int fno_timing_enable(int on) {
   g_timing_on = on != 0;
   g_timing_used = 0;

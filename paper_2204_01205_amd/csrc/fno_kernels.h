@@ -75,6 +75,15 @@ hipError_t launch_pointwise_mlp2(int B, int Ci, int H, int Co, int64_t np, const
 hipError_t launch_time_lift(int B, int Ci, int Co, int64_t np, int Nt, const float* a, const float* wt,
                             const float* bt, const float* wc, const float* bc, float* out, hipStream_t s);
 
+// Relative L2 misfit ||pred - target|| / ||target|| (device scalar `loss`, nullable) and its
+// gradient with respect to pred (nullable); ws: rel_l2_workspace_bytes() of scratch.
+size_t rel_l2_workspace_bytes();
+hipError_t launch_rel_l2(int64_t n, const float* pred, const float* target, float* loss, float* grad,
+                         double* ws, hipStream_t s);
+// One Adam step in place on n floats (complex parameters as pairs of floats); step counts from 1.
+hipError_t launch_adam(int64_t n, float* p, const float* g, float* m, float* v, double lr, double beta1,
+                       double beta2, double eps, int step, hipStream_t s);
+
 // Limits of the kernels (checked by the API before any launch).
 constexpr int kMaxFftM = 32;        // largest in-register FFT
 constexpr int kMaxCo = 32;          // accumulator file of the epilogue

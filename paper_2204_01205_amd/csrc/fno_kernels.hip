@@ -10,6 +10,7 @@
 // the residue classes n = P*n1 + n2, then a P-term twiddle combine evaluated only at the kept
 // frequencies.  M = 1 degenerates to a dense truncated DFT and covers any axis length.
 #include "fno_kernels.h"
+#include <cmath>
 #include "fft_reg.h"
 
 namespace fno {
@@ -1420,6 +1421,73 @@ __global__ __launch_bounds__(kThreads) void pointwise_linear_kernel(
     if (o < Co) y[(b * Co + o) * np + p] = acc[o];
 }
 
+// ------------------------------------------------------------------------------------------
+// Training pieces outside the block (Sec. 4): relative L2 misfit and the Adam update
+// ------------------------------------------------------------------------------------------
+constexpr int kLossBlocks = 1024;      // partial sums of the loss (two doubles each)
+
+// part[blk] = (sum (pred - target)^2, sum target^2) over the block's strided share, in double,
+// combined in a fixed order (lane tree, then waves in order): same bits on every run.
+__global__ __launch_bounds__(kThreads) void rel_l2_partial_kernel(
+    long long n, const float* __restrict__ pred, const float* __restrict__ target, double* __restrict__ part) {
+  __shared__ double sd[kThreads / 64], sy[kThreads / 64];
+  double d2 = 0.0, y2 = 0.0;
+  for (long long i = (long long)blockIdx.x * kThreads + threadIdx.x; i < n; i += (long long)gridDim.x * kThreads) {
+    const double y = target[i];
+    const double d = (double)pred[i] - y;
+    d2 += d * d;
+    y2 += y * y;
+  }
+#pragma unroll
+  for (int off = 32; off >= 1; off >>= 1) {
+    d2 += __shfl_xor(d2, off);
+    y2 += __shfl_xor(y2, off);
+  }
+  if ((threadIdx.x & 63) == 0) { sd[threadIdx.x >> 6] = d2; sy[threadIdx.x >> 6] = y2; }
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    double a = 0.0, b = 0.0;
+    for (int w = 0; w < kThreads / 64; ++w) { a += sd[w]; b += sy[w]; }
+    part[2 * blockIdx.x] = a;
+    part[2 * blockIdx.x + 1] = b;
+  }
+}
+
+// loss = sqrt(Sd) / sqrt(Sy); scale = 1 / (sqrt(Sd) sqrt(Sy)) for the gradient (0 when Sd = 0)
+__global__ void rel_l2_final_kernel(const double* __restrict__ part, int nblk, float* __restrict__ loss,
+                                    double* __restrict__ scale) {
+  if (threadIdx.x != 0 || blockIdx.x != 0) return;
+  double a = 0.0, b = 0.0;
+  for (int i = 0; i < nblk; ++i) { a += part[2 * i]; b += part[2 * i + 1]; }
+  const double nd = sqrt(a), ny = sqrt(b);
+  if (loss != nullptr) *loss = (float)(nd / ny);
+  *scale = nd > 0.0 ? 1.0 / (nd * ny) : 0.0;
+}
+
+__global__ __launch_bounds__(kThreads) void rel_l2_grad_kernel(
+    long long n, const float* __restrict__ pred, const float* __restrict__ target,
+    const double* __restrict__ scale, float* __restrict__ grad) {
+  const float sc = (float)*scale;
+  for (long long i = (long long)blockIdx.x * kThreads + threadIdx.x; i < n; i += (long long)gridDim.x * kThreads)
+    grad[i] = (pred[i] - target[i]) * sc;
+}
+
+// Adam (Kingma & Ba, Algorithm 1), one step in place; c1 = 1 / (1 - beta1^t), c2 = 1 / (1 - beta2^t)
+__global__ __launch_bounds__(kThreads) void adam_kernel(
+    long long n, float* __restrict__ p, const float* __restrict__ g, float* __restrict__ m,
+    float* __restrict__ v, float lr, float beta1, float omb1, float beta2, float omb2, float eps, float c1,
+    float c2) {
+  // omb = 1 - beta, rounded from double on the host (1 - beta in float would lose five digits)
+  for (long long i = (long long)blockIdx.x * kThreads + threadIdx.x; i < n; i += (long long)gridDim.x * kThreads) {
+    const float gi = g[i];
+    const float mi = fmaf(beta1, m[i], omb1 * gi);
+    const float vi = fmaf(beta2, v[i], omb2 * gi * gi);
+    m[i] = mi;
+    v[i] = vi;
+    p[i] -= lr * (mi * c1) / (sqrtf(vi * c2) + eps);
+  }
+}
+
 // Input lifts of Sec. 2.4 (eqs. (8)-(9)) in one sweep: a_1 = W_t a + b_t along a time axis of
 // length one, then nu = W_c a_1 + b_c along the channels, i.e.
 //   nu[b][c][p][t] = W_t[t] s_c(p) + b_t[t] r_c + b_c[c],  s_c(p) = sum_j W_c[c][j] a[b][j][p],
@@ -1974,6 +2042,37 @@ hipError_t launch_time_lift(int B, int Ci, int Co, int64_t np, int Nt, const flo
   else
     hipLaunchKernelGGL((time_lift_kernel<32>), grid, dim3(kThreads), 0, s, Ci, Co, (long long)np, Nt, a, wt,
                        bt, wc, bc, out);
+  return hipGetLastError();
+}
+
+size_t rel_l2_workspace_bytes() { return (size_t)(2 * kLossBlocks + 1) * sizeof(double); }
+
+hipError_t launch_rel_l2(int64_t n, const float* pred, const float* target, float* loss, float* grad,
+                         double* ws, hipStream_t s) {
+  if (n <= 0) return hipErrorInvalidValue;
+  int nblk = (int)((n + kThreads - 1) / kThreads);
+  if (nblk > kLossBlocks) nblk = kLossBlocks;
+  double* scale = ws + 2 * kLossBlocks;
+  hipLaunchKernelGGL(rel_l2_partial_kernel, dim3(nblk), dim3(kThreads), 0, s, (long long)n, pred, target, ws);
+  hipLaunchKernelGGL(rel_l2_final_kernel, dim3(1), dim3(64), 0, s, ws, nblk, loss, scale);
+  if (grad != nullptr) {
+    int64_t gb = (n + kThreads - 1) / kThreads;
+    if (gb > 65536) gb = 65536;
+    hipLaunchKernelGGL(rel_l2_grad_kernel, dim3((unsigned)gb), dim3(kThreads), 0, s, (long long)n, pred, target,
+                       scale, grad);
+  }
+  return hipGetLastError();
+}
+
+hipError_t launch_adam(int64_t n, float* p, const float* g, float* m, float* v, double lr, double beta1,
+                       double beta2, double eps, int step, hipStream_t s) {
+  if (n <= 0) return hipSuccess;
+  const float c1 = (float)(1.0 / (1.0 - pow(beta1, (double)step)));
+  const float c2 = (float)(1.0 / (1.0 - pow(beta2, (double)step)));
+  int64_t nb = (n + kThreads - 1) / kThreads;
+  if (nb > 65536) nb = 65536;
+  hipLaunchKernelGGL(adam_kernel, dim3((unsigned)nb), dim3(kThreads), 0, s, (long long)n, p, g, m, v, (float)lr,
+                     (float)beta1, (float)(1.0 - beta1), (float)beta2, (float)(1.0 - beta2), (float)eps, c1, c2);
   return hipGetLastError();
 }
 

@@ -324,3 +324,48 @@ def test_time_lift_matches_oracle(shape):
     B.fno_time_lift(batch, c_in, c_out, nspace, nt, dev(a), dev(wt), None, dev(wc), None, out)
     torch.cuda.synchronize()
     assert rel(host(out), O.time_lift(a, wt, np.zeros(nt), wc, np.zeros(c_out))) <= TOL
+
+
+@pytest.mark.parametrize("n", [7, 100003, 60 * 60 * 64 * 30])
+def test_relative_l2_loss_and_gradient_match_oracle(n):
+    rng = np.random.default_rng([11, n])
+    target = rng.standard_normal(n).astype(np.float32)
+    pred = (target + 0.3 * rng.standard_normal(n)).astype(np.float32)
+    ws = torch.empty(B.fno_rel_l2_workspace_bytes() // 4, dtype=torch.float32, device="cuda")
+    loss = torch.empty(1, device="cuda")
+    grad = torch.empty(n, device="cuda")
+    B.fno_rel_l2_loss(n, dev(pred), dev(target), loss, grad, ws)
+    torch.cuda.synchronize()
+    want = O.rel_l2_loss(pred, target)
+    assert abs(float(loss.cpu()) - want) <= TOL * want
+    assert rel(host(grad), O.rel_l2_grad(pred, target)) <= TOL
+    # same bits on a second run; loss alone; a perfect prediction has loss 0 and a zero gradient
+    loss2 = torch.empty(1, device="cuda")
+    B.fno_rel_l2_loss(n, dev(pred), dev(target), loss2, None, ws)
+    B.fno_rel_l2_loss(n, dev(target), dev(target), loss, grad, ws)
+    torch.cuda.synchronize()
+    assert abs(float(loss2.cpu()) - want) <= TOL * want
+    assert float(loss.cpu()) == 0.0 and not bool(grad.any())
+
+
+def test_adam_steps_match_oracle_for_real_and_complex_parameters():
+    rng = np.random.default_rng(13)
+    w = rng.standard_normal((20, 20)).astype(np.float32)
+    r = (rng.standard_normal((3, 3, 4, 4, 4, 3)) + 1j * rng.standard_normal((3, 3, 4, 4, 4, 3))).astype(np.complex64)
+    for p0 in (w, r):
+        as_real = p0.view(np.float32).ravel() if np.iscomplexobj(p0) else p0.ravel()
+        n = as_real.size
+        p = dev(as_real.copy())
+        m = torch.zeros(n, device="cuda")
+        v = torch.zeros(n, device="cuda")
+        po, mo, vo = as_real.astype(np.float64), np.zeros(n), np.zeros(n)
+        for step in (1, 2, 3):
+            g = (rng.standard_normal(n) * (10.0 ** rng.integers(-3, 2))).astype(np.float32)
+            B.fno_adam_step(n, p, dev(g), m, v, 1e-3, 0.9, 0.999, 1e-8, step)
+            before = po
+            po, mo, vo = O.adam_step(po, g, mo, vo, step)
+            torch.cuda.synchronize()
+            assert rel(host(m), mo) <= TOL and rel(host(v), vo) <= TOL
+            assert rel(host(p), po) <= TOL
+            # the update itself, not only the updated parameter
+            assert rel(host(p).astype(np.float64) - before, po - before) <= 1e-3
