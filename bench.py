@@ -26,7 +26,7 @@ def parse():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=10)
     ap.add_argument("--warmup", type=int, default=3)
-    ap.add_argument("--config", default="cfg4", help="workload name from synth.CONFIGS (block forward)")
+    ap.add_argument("--config", default="cfg4", help="workload name from synth.CONFIGS (block forward; cfg5: forward + backward), or time_lift")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="only run plain device copies of 4 GiB (reference reading for rocprofv3 --pmc "
@@ -63,6 +63,52 @@ def cpu_baseline(cfg):
             "host_cores_visible": len(os.sched_getaffinity(0))}
 
 
+def time_lift_bench(args, torch, B):
+    """The fused input lifts (fno_time_lift) at the largest grid: 2 -> 20 channels, 1 -> 32 time steps."""
+    grid, nt, c_in, c_out = (256, 256, 128), 32, 2, 20
+    ns = grid[0] * grid[1] * grid[2]
+    torch.cuda.set_device(0)
+    gen = torch.Generator(device="cuda")
+    gen.manual_seed(0)
+    a = torch.randn((1, c_in, ns), device="cuda", generator=gen)
+    wt = torch.randn(nt, device="cuda", generator=gen)
+    bt = torch.randn(nt, device="cuda", generator=gen)
+    wc = torch.randn((c_out, c_in), device="cuda", generator=gen)
+    bc = torch.randn(c_out, device="cuda", generator=gen)
+    out = torch.empty((1, c_out, ns, nt), device="cuda")
+
+    def step():
+        B.fno_time_lift(1, c_in, c_out, ns, nt, a, wt, bt, wc, bc, out)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    t0 = time.perf_counter()
+    e0.record()                      # the launches go to torch's current stream, which these events see
+    for _ in range(args.steps):
+        step()
+    e1.record()
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    ms = 1e3 * dt / args.steps
+    launch_ms = e0.elapsed_time(e1) / args.steps
+    pc = float(c_out) * ns * nt
+    nbytes = 4.0 * pc + 4.0 * c_in * ns          # output written once, input read once
+    print(json.dumps({
+        "metric": "FNO spectral layer Gpoint-channels/s + achieved HBM GB/s on 1 MI355X",
+        "value": pc / (ms * 1e-3) / 1e9, "unit": "Gpoint-channels/s", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": ms, "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+        "config": {"workload": f"time_lift: fno_time_lift, batch 1, {c_in} -> {c_out} channels, grid "
+                               f"{grid[0]}x{grid[1]}x{grid[2]}, 1 -> {nt} time steps",
+                   "global_batch": 1, "parallelism": "single GPU"},
+        "roofline": {"kernel": "time_lift", "bound": "hbm", "achieved": nbytes / (launch_ms * 1e-3) / 1e9,
+                     "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": nbytes / (launch_ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
+                     "traffic": None, "avg_launch_ms": launch_ms, "algorithmic_bytes_per_launch": nbytes},
+    }))
+
+
 def main():
     args = parse()
     if args.gpus != 1:
@@ -81,6 +127,9 @@ def main():
             dst.copy_(src)
         torch.cuda.synchronize()
         print(json.dumps({"calibrate_copy_bytes_each_way": 4 * (1 << 30), "copies": 3}))
+        return
+    if args.config == "time_lift":
+        time_lift_bench(args, torch, B)
         return
     cfg = synth.CONFIGS[args.config]
     batch, width, grid, modes = cfg["batch"], cfg["width"], tuple(cfg["grid"]), tuple(cfg["modes"])
