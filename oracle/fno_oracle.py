@@ -462,6 +462,43 @@ def pointwise_mlp2(x, w1, b1, w2, b2):
     return channel_affine(gelu(channel_affine(x, w1, b1)), w2, b2)
 
 
+def pointwise_linear_bwd(x, w, g):
+    """Adjoint of y = W x + b along channels: gx = W^T g; gW and gb are sums over batch and points
+    (the adjoint of broadcasting W and b, Sec. 2.1)."""
+    x, w, g = np.asarray(x, np.float64), np.asarray(w, np.float64), np.asarray(g, np.float64)
+    gx = np.moveaxis(np.tensordot(w, g, axes=([0], [1])), 0, 1)            # (b, i, grid)
+    axes = [0] + list(range(2, g.ndim))
+    gw = np.tensordot(g, x, axes=(axes, axes))                              # (o, i)
+    return {"gx": gx, "gW": gw, "gb": g.sum(axis=tuple(axes))}
+
+
+def pointwise_mlp2_bwd(x, w1, b1, w2, g):
+    """Adjoint of u = W2 sigma(W1 x + b1) + b2 for a cotangent g of u, by the chain rule."""
+    h = channel_affine(x, w1, b1)
+    outer = pointwise_linear_bwd(gelu(h), w2, g)          # through W2: gives g_a, gW2, gb2
+    gh = outer["gx"] * gelu_prime(h)
+    inner = pointwise_linear_bwd(x, w1, gh)               # through W1: gives gx, gW1, gb1
+    return {"gx": inner["gx"], "gW1": inner["gW"], "gb1": inner["gb"], "gW2": outer["gW"], "gb2": outer["gb"]}
+
+
+def fno_backward(a, lift_w, lift_b, blocks, proj, spec: LayerSpec, gu):
+    """Gradients of the whole network (lift, blocks of eq. (2), projection) for a cotangent gu of
+    its output: the forward is replayed keeping each block's input, then the chain runs backwards."""
+    w1, b1, w2, _ = proj
+    vs = [pointwise_linear(a, lift_w, lift_b)]
+    for (r, w, b) in blocks:
+        vs.append(block_fwd(vs[-1], r, w, b, spec, "gelu")[0])
+    gp = pointwise_mlp2_bwd(vs[-1], w1, b1, w2, gu)
+    grads = {"proj": gp, "blocks": []}
+    gv = gp["gx"]
+    for (r, w, b), vin in zip(reversed(blocks), reversed(vs[:-1])):
+        gb_ = block_bwd(vin, r, w, b, gv, spec, "gelu")
+        grads["blocks"].insert(0, gb_)
+        gv = gb_["gx"]
+    grads["lift"] = pointwise_linear_bwd(a, lift_w, gv)
+    return grads
+
+
 def fno_forward(a, lift_w, lift_b, blocks, proj, spec: LayerSpec):
     """Lift, K blocks of eq. (2), projection.  blocks: list of (R, W, b); proj: (w1,b1,w2,b2)."""
     v = pointwise_linear(a, lift_w, lift_b)

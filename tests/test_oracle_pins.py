@@ -542,3 +542,83 @@ def test_adam_step_against_closed_forms():
         vi = 0.99 * v1[i] + 0.01 * g[i] ** 2
         want = p0[i] - 2e-3 * (mi / (1 - 0.8 ** 3)) / (math.sqrt(vi / (1 - 0.99 ** 3)) + 1e-6)
         assert abs(q[i] - want) <= 1e-14 and abs(mq[i] - mi) <= 1e-15 and abs(vq[i] - vi) <= 1e-15
+
+
+def test_pointwise_adjoints_against_loops_and_finite_differences():
+    rng = np.random.default_rng(17)
+    B_, Ci, H, Co, grid = 2, 3, 5, 2, (2, 1, 2, 3)
+    x = rng.standard_normal((B_, Ci) + grid)
+    w = rng.standard_normal((H, Ci))
+    g = rng.standard_normal((B_, H) + grid)
+    got = O.pointwise_linear_bwd(x, w, g)
+    # plain loops
+    gw = np.zeros((H, Ci)); gb = np.zeros(H); gx = np.zeros_like(x)
+    for b in range(B_):
+        for idx in np.ndindex(*grid):
+            for o in range(H):
+                gb[o] += g[(b, o) + idx]
+                for i in range(Ci):
+                    gw[o, i] += g[(b, o) + idx] * x[(b, i) + idx]
+                    gx[(b, i) + idx] += w[o, i] * g[(b, o) + idx]
+    assert np.max(np.abs(got["gW"] - gw)) <= 1e-13 and np.max(np.abs(got["gb"] - gb)) <= 1e-13
+    assert np.max(np.abs(got["gx"] - gx)) <= 1e-13
+    # two-layer projection: directional derivatives of S = <gu, mlp2(x; w1, b1, w2, b2)>
+    w1, b1 = rng.standard_normal((H, Ci)), rng.standard_normal(H)
+    w2, b2 = rng.standard_normal((Co, H)), rng.standard_normal(Co)
+    gu = rng.standard_normal((B_, Co) + grid)
+    grads = O.pointwise_mlp2_bwd(x, w1, b1, w2, gu)
+    S = lambda x_, w1_, b1_, w2_, b2_: float(np.sum(gu * O.pointwise_mlp2(x_, w1_, b1_, w2_, b2_)))
+    eps = 1e-6
+    for name, base, grad in (("x", x, grads["gx"]), ("w1", w1, grads["gW1"]), ("b1", b1, grads["gb1"]),
+                             ("w2", w2, grads["gW2"]), ("b2", b2, grads["gb2"])):
+        d = rng.standard_normal(base.shape)
+        args_p = {"x": x, "w1": w1, "b1": b1, "w2": w2, "b2": b2}
+        args_m = dict(args_p)
+        args_p[name] = base + eps * d
+        args_m[name] = base - eps * d
+        fd = (S(args_p["x"], args_p["w1"], args_p["b1"], args_p["w2"], args_p["b2"])
+              - S(args_m["x"], args_m["w1"], args_m["b1"], args_m["w2"], args_m["b2"])) / (2 * eps)
+        an = float(np.sum(grad * d))
+        assert abs(fd - an) <= 1e-8 + 1e-7 * abs(an), name
+
+
+def test_whole_network_gradient_by_finite_differences():
+    """fno_backward against central differences of S = <gu, fno_forward(...)> in random directions."""
+    rng = np.random.default_rng(23)
+    spec = O.LayerSpec((4, 4, 4, 4), (1, 1, 1, 2), 0)
+    counts = tuple(len(k) for k in O.mode_lists(spec))
+    Cin, C, H = 2, 3, 4
+    a = rng.standard_normal((1, Cin) + spec.grid)
+    lw, lb = rng.standard_normal((C, Cin)), rng.standard_normal(C)
+    blocks = []
+    for _ in range(2):
+        r = (rng.standard_normal((C, C) + counts) + 1j * rng.standard_normal((C, C) + counts)) / C
+        blocks.append((r, rng.standard_normal((C, C)) / np.sqrt(C), 0.1 * rng.standard_normal(C)))
+    proj = (rng.standard_normal((H, C)), rng.standard_normal(H), rng.standard_normal((1, H)), rng.standard_normal(1))
+    gu = rng.standard_normal((1, 1) + spec.grid)
+    grads = O.fno_backward(a, lw, lb, blocks, proj, spec, gu)
+    S = lambda lw_, blocks_, proj_: float(np.sum(gu * O.fno_forward(a, lw_, lb, blocks_, proj_, spec)))
+    eps = 1e-6
+    # lift weight
+    d = rng.standard_normal(lw.shape)
+    fd = (S(lw + eps * d, blocks, proj) - S(lw - eps * d, blocks, proj)) / (2 * eps)
+    an = float(np.sum(grads["lift"]["gW"] * d))
+    assert abs(fd - an) <= 1e-8 + 1e-6 * abs(an)
+    # the first block's spectral weight (real and imaginary directions) and pointwise weight
+    r0, w0, b0 = blocks[0]
+    dr = rng.standard_normal(r0.shape) + 1j * rng.standard_normal(r0.shape)
+    bp = [(r0 + eps * dr, w0, b0), blocks[1]]
+    bm = [(r0 - eps * dr, w0, b0), blocks[1]]
+    fd = (S(lw, bp, proj) - S(lw, bm, proj)) / (2 * eps)
+    gR = grads["blocks"][0]["gR"]
+    an = float(np.sum(gR.real * dr.real + gR.imag * dr.imag))
+    assert abs(fd - an) <= 1e-8 + 1e-6 * abs(an)
+    dw = rng.standard_normal(w0.shape)
+    fd = (S(lw, [(r0, w0 + eps * dw, b0), blocks[1]], proj) - S(lw, [(r0, w0 - eps * dw, b0), blocks[1]], proj)) / (2 * eps)
+    an = float(np.sum(grads["blocks"][0]["gW"] * dw))
+    assert abs(fd - an) <= 1e-8 + 1e-6 * abs(an)
+    # projection, first layer
+    d1 = rng.standard_normal(proj[0].shape)
+    fd = (S(lw, blocks, (proj[0] + eps * d1,) + proj[1:]) - S(lw, blocks, (proj[0] - eps * d1,) + proj[1:])) / (2 * eps)
+    an = float(np.sum(grads["proj"]["gW1"] * d1))
+    assert abs(fd - an) <= 1e-8 + 1e-6 * abs(an)
