@@ -137,6 +137,25 @@ int fno_time_lift(int32_t batch, int32_t c_in, int32_t c_out, int64_t nspace, in
                   const float* Wt, const float* bt, const float* Wc, const float* bc, float* out,
                   void* stream);
 
+/* Adjoints of fno_pointwise_linear and fno_pointwise_mlp2 (what the backward of a whole network
+ * needs around its blocks).  For a cotangent g of the output:
+ *   linear:  gx = W^T g  [B][c_in][npoints];  gW[o][i] = sum g[b][o][p] x[b][i][p];  gb[o] = sum g
+ *   mlp2:    with h = W1 x + b1:  gW2[o][k] = sum g_o gelu(h_k), gb2 = sum g,
+ *            gh = (W2^T g) gelu'(h), gW1[k][i] = sum gh_k x_i, gb1 = sum gh, gx = W1^T gh.
+ * The sums run over all batch entries and points (the adjoint of broadcasting the weights,
+ * Sec. 2.1) in a fixed order: the same bits on every run.  Every output is nullable and
+ * overwritten.  ws: device scratch of fno_pointwise_bwd_workspace_bytes(c_in, hidden, c_out)
+ * bytes (hidden = 0 for the linear map), 8-byte aligned, owned by the caller.  Widths: c_in,
+ * c_out <= 32 (linear); c_in <= 32, c_out <= 4, hidden <= 1024 (mlp2). */
+int fno_pointwise_bwd_workspace_bytes(int32_t c_in, int32_t hidden, int32_t c_out, size_t* bytes);
+int fno_pointwise_linear_bwd(int32_t batch, int32_t c_in, int32_t c_out, int64_t npoints, const float* x,
+                             const float* W, const float* g, float* gx, float* gW, float* gb, void* ws,
+                             size_t ws_bytes, void* stream);
+int fno_pointwise_mlp2_bwd(int32_t batch, int32_t c_in, int32_t hidden, int32_t c_out, int64_t npoints,
+                           const float* x, const float* W1, const float* b1, const float* W2, const float* g,
+                           float* gx, float* gW1, float* gb1, float* gW2, float* gb2, void* ws,
+                           size_t ws_bytes, void* stream);
+
 /* Relative L2 misfit of Sec. 4 over n floats:  loss = ||pred - target||_2 / ||target||_2, written to
  * the device scalar `loss` (nullable), and its gradient with respect to pred,
  * (pred - target) / (||pred - target||_2 ||target||_2), written to grad (nullable, n floats; all

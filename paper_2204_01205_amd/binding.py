@@ -25,6 +25,7 @@ EXPORTS = [
     "fno_workspace_bytes", "fno_mode_indices", "fno_spectral_conv_fwd", "fno_spectral_conv_bwd",
     "fno_block_fwd", "fno_block_bwd", "fno_pointwise_linear", "fno_pointwise_mlp2", "fno_time_lift",
     "fno_rel_l2_workspace_bytes", "fno_rel_l2_loss", "fno_adam_step",
+    "fno_pointwise_bwd_workspace_bytes", "fno_pointwise_linear_bwd", "fno_pointwise_mlp2_bwd",
     "fno_status_string", "fno_timing_enable", "fno_timing_read",
 ]
 
@@ -164,6 +165,31 @@ def fno_time_lift(batch, c_in, c_out, nspace, nt, a, Wt, bt, Wc, bc, out) -> Non
                                ctypes.c_int64(nspace), ctypes.c_int32(nt), _ptr(a, name="a"),
                                _ptr(Wt, name="Wt"), _ptr(bt, name="bt"), _ptr(Wc, name="Wc"),
                                _ptr(bc, name="bc"), _ptr(out, name="out"), _stream()))
+
+
+def fno_pointwise_bwd_workspace_bytes(c_in, hidden, c_out) -> int:
+    n = ctypes.c_size_t(0)
+    _check(lib().fno_pointwise_bwd_workspace_bytes(ctypes.c_int32(c_in), ctypes.c_int32(hidden),
+                                                   ctypes.c_int32(c_out), ctypes.byref(n)))
+    return int(n.value)
+
+
+def fno_pointwise_linear_bwd(batch, c_in, c_out, npoints, x, W, g, gx, gW, gb, ws) -> None:
+    _check(lib().fno_pointwise_linear_bwd(ctypes.c_int32(batch), ctypes.c_int32(c_in), ctypes.c_int32(c_out),
+                                          ctypes.c_int64(npoints), _ptr(x, name="x"), _ptr(W, name="W"),
+                                          _ptr(g, name="g"), _ptr(gx, name="gx"), _ptr(gW, name="gW"),
+                                          _ptr(gb, name="gb"), _ptr(ws, name="ws"),
+                                          ctypes.c_size_t(ws.numel() * ws.element_size()), _stream()))
+
+
+def fno_pointwise_mlp2_bwd(batch, c_in, hidden, c_out, npoints, x, W1, b1, W2, g, gx, gW1, gb1, gW2, gb2, ws) -> None:
+    _check(lib().fno_pointwise_mlp2_bwd(ctypes.c_int32(batch), ctypes.c_int32(c_in), ctypes.c_int32(hidden),
+                                        ctypes.c_int32(c_out), ctypes.c_int64(npoints), _ptr(x, name="x"),
+                                        _ptr(W1, name="W1"), _ptr(b1, name="b1"), _ptr(W2, name="W2"),
+                                        _ptr(g, name="g"), _ptr(gx, name="gx"), _ptr(gW1, name="gW1"),
+                                        _ptr(gb1, name="gb1"), _ptr(gW2, name="gW2"), _ptr(gb2, name="gb2"),
+                                        _ptr(ws, name="ws"), ctypes.c_size_t(ws.numel() * ws.element_size()),
+                                        _stream()))
 
 
 def fno_rel_l2_workspace_bytes() -> int:

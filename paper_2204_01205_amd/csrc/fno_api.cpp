@@ -386,6 +386,39 @@ int fno_time_lift(int32_t batch, int32_t c_in, int32_t c_out, int64_t nspace, in
   return FNO_OK;
 }
 
+int fno_pointwise_bwd_workspace_bytes(int32_t c_in, int32_t hidden, int32_t c_out, size_t* bytes) {
+  if (bytes == nullptr || c_in < 1 || hidden < 0 || c_out < 1) { set_detail("positive widths and bytes are required"); return FNO_EINVAL; }
+  *bytes = fno::pointwise_bwd_workspace_bytes(c_in, hidden, c_out);
+  return FNO_OK;
+}
+
+int fno_pointwise_linear_bwd(int32_t batch, int32_t c_in, int32_t c_out, int64_t npoints, const float* x,
+                             const float* W, const float* g, float* gx, float* gW, float* gb, void* ws,
+                             size_t ws_bytes, void* stream) {
+  if (batch < 1 || c_in < 1 || c_out < 1 || npoints < 1) { set_detail("sizes must be positive"); return FNO_EINVAL; }
+  if (x == nullptr || W == nullptr || g == nullptr || ws == nullptr) { set_detail("x, W, g and ws are required"); return FNO_EINVAL; }
+  if (c_in > 32 || c_out > 32 || batch > 65535) { set_detail("pointwise_linear_bwd covers widths <= 32, batch <= 65535"); return FNO_EUNSUPPORTED; }
+  if (ws_bytes < fno::pointwise_bwd_workspace_bytes(c_in, 0, c_out)) { set_detail("workspace too small"); return FNO_ENOSPC; }
+  if (reinterpret_cast<uintptr_t>(ws) % 8 != 0) { set_detail("ws must be 8-byte aligned"); return FNO_EINVAL; }
+  FNO_HIP(fno::launch_pointwise_linear_bwd(batch, c_in, c_out, npoints, x, W, g, gx, gW, gb, ws,
+                                           static_cast<hipStream_t>(stream)));
+  return FNO_OK;
+}
+
+int fno_pointwise_mlp2_bwd(int32_t batch, int32_t c_in, int32_t hidden, int32_t c_out, int64_t npoints,
+                           const float* x, const float* W1, const float* b1, const float* W2, const float* g,
+                           float* gx, float* gW1, float* gb1, float* gW2, float* gb2, void* ws,
+                           size_t ws_bytes, void* stream) {
+  if (batch < 1 || c_in < 1 || hidden < 1 || c_out < 1 || npoints < 1) { set_detail("sizes must be positive"); return FNO_EINVAL; }
+  if (x == nullptr || W1 == nullptr || W2 == nullptr || g == nullptr || ws == nullptr) { set_detail("x, W1, W2, g and ws are required"); return FNO_EINVAL; }
+  if (c_in > 32 || c_out > 4 || hidden > 1024) { set_detail("pointwise_mlp2_bwd covers c_in <= 32, c_out <= 4, hidden <= 1024"); return FNO_EUNSUPPORTED; }
+  if (ws_bytes < fno::pointwise_bwd_workspace_bytes(c_in, hidden, c_out)) { set_detail("workspace too small"); return FNO_ENOSPC; }
+  if (reinterpret_cast<uintptr_t>(ws) % 8 != 0) { set_detail("ws must be 8-byte aligned"); return FNO_EINVAL; }
+  FNO_HIP(fno::launch_pointwise_mlp2_bwd(batch, c_in, hidden, c_out, npoints, x, W1, b1, W2, g, gx, gW1, gb1, gW2,
+                                         gb2, ws, static_cast<hipStream_t>(stream)));
+  return FNO_OK;
+}
+
 int fno_rel_l2_workspace_bytes(size_t* bytes) {
   if (bytes == nullptr) { set_detail("bytes is required"); return FNO_EINVAL; }
   *bytes = fno::rel_l2_workspace_bytes();

@@ -84,6 +84,16 @@ hipError_t launch_rel_l2(int64_t n, const float* pred, const float* target, floa
 hipError_t launch_adam(int64_t n, float* p, const float* g, float* m, float* v, double lr, double beta1,
                        double beta2, double eps, int step, hipStream_t s);
 
+// Adjoints of the channel lift and of the two-layer projection.  ws: pointwise_bwd_workspace_bytes()
+// of scratch, 8-byte aligned.  Outputs nullable.
+size_t pointwise_bwd_workspace_bytes(int Ci, int H, int Co);
+hipError_t launch_pointwise_linear_bwd(int B, int Ci, int Co, int64_t N, const float* x, const float* W,
+                                       const float* g, float* gx, float* gW, float* gb, void* ws,
+                                       hipStream_t s);
+hipError_t launch_pointwise_mlp2_bwd(int B, int Ci, int H, int Co, int64_t N, const float* x, const float* W1,
+                                     const float* b1, const float* W2, const float* g, float* gx, float* gW1,
+                                     float* gb1, float* gW2, float* gb2, void* ws, hipStream_t s);
+
 // Limits of the kernels (checked by the API before any launch).
 constexpr int kMaxFftM = 32;        // largest in-register FFT
 constexpr int kMaxCo = 32;          // accumulator file of the epilogue

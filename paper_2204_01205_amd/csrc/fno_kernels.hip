@@ -1228,11 +1228,11 @@ __global__ __launch_bounds__(kThreads) void bwd_pointwise_kernel(
       float gv = 0.f;
       if (live) {
         const long long e = (b * Co + o) * N + p;
-        const float zv = z[e];
+        const float zv = (act || mse_target) ? z[e] : 0.f;
         float g = gout[e];
         if (mse_target) g = mse_scale * ((act ? gelu_f(zv) : zv) - g);
         gv = act ? g * gelu_prime_f(zv) : g;
-        gz_out[e] = gv;
+        if (gz_out != nullptr) gz_out[e] = gv;
       }
       Gs[o * sR + tid] = gv;
     }
@@ -1419,6 +1419,139 @@ __global__ __launch_bounds__(kThreads) void pointwise_linear_kernel(
 #pragma unroll
   for (int o = 0; o < CO; ++o)
     if (o < Co) y[(b * Co + o) * np + p] = acc[o];
+}
+
+// ------------------------------------------------------------------------------------------
+// Adjoints of the lift and of the projection (what a whole-network backward needs around the
+// blocks): sums over all points in a fixed order, per-block partials in double
+// ------------------------------------------------------------------------------------------
+__global__ void transpose_kernel(const float* __restrict__ w, float* __restrict__ wt, int rows, int cols) {
+  const int idx = blockIdx.x * blockDim.x + threadIdx.x;
+  if (idx < rows * cols) wt[(idx % cols) * rows + idx / cols] = w[idx];
+}
+
+// out[q] = sum over blocks of part[blk][q], blocks in order (same bits on every run); the result
+// goes to four destinations by ranges of q (any of them may be null)
+__global__ __launch_bounds__(kThreads) void reduce_ranges_kernel(
+    const double* __restrict__ part, int nblk, int n0, int n1, int n2, int n3, float* __restrict__ d0,
+    float* __restrict__ d1, float* __restrict__ d2, float* __restrict__ d3) {
+  const int q = blockIdx.x * kThreads + threadIdx.x;
+  const int npairs = n0 + n1 + n2 + n3;
+  if (q >= npairs) return;
+  double s = 0.0;
+  for (int b = 0; b < nblk; ++b) s += part[(long long)b * npairs + q];
+  if (q < n0) { if (d0 != nullptr) d0[q] = (float)s; }
+  else if (q < n0 + n1) { if (d1 != nullptr) d1[q - n0] = (float)s; }
+  else if (q < n0 + n1 + n2) { if (d2 != nullptr) d2[q - n0 - n1] = (float)s; }
+  else if (d3 != nullptr) d3[q - n0 - n1 - n2] = (float)s;
+}
+
+// Adjoint of u = W2 gelu(W1 x + b1) + b2 per point.  One block: tiles of 256 points.  The hidden
+// units are taken kMlpChunk at a time: every thread computes, for its point, h, a = gelu(h) and
+// gh = (W2^T g) gelu'(h) of the chunk into LDS and adds W1^T gh to its gx; then the threads take
+// one (row, row) pair each of the chunk's sums -- gW1[k][i] = sum gh_k x_i, gb1[k] = sum gh_k,
+// gW2[o][k] = sum g_o a_k -- as a 256-term inner product in float, added to the block's double
+// accumulator of that pair in LDS (one owner per pair: no atomics, fixed order).
+constexpr int kMlpChunk = 8;
+constexpr int kMlpBlocks = 512;     // blocks (= partial-sum slots) of the projection's backward
+template <int CI>
+__global__ __launch_bounds__(kThreads) void mlp2_bwd_kernel(
+    int B, int Ci, int H, int Co, long long N, const float* __restrict__ x, const float* __restrict__ W1,
+    const float* __restrict__ b1, const float* __restrict__ W2, const float* __restrict__ g,
+    float* __restrict__ gx, double* __restrict__ part) {
+  HIP_DYNAMIC_SHARED(float, smem)
+  constexpr int sR = kThreads + 1;
+  float* XS = smem;                          // [Ci][sR]
+  float* GS = XS + Ci * sR;                  // [Co][sR]
+  float* GH = GS + Co * sR;                  // [kMlpChunk][sR]
+  float* AA = GH + kMlpChunk * sR;           // [kMlpChunk][sR]
+  const int nsum = H * (Ci + 1) + Co * H + Co;       // gW1 | gb1 | gW2 | gb2
+  int acc_off = (Ci + Co + 2 * kMlpChunk) * sR;
+  acc_off += acc_off & 1;
+  double* ACC = reinterpret_cast<double*>(smem + acc_off);   // [nsum]
+  const int tid = threadIdx.x;
+  for (int q = tid; q < nsum; q += kThreads) ACC[q] = 0.0;
+  const long long tiles_per_b = (N + kThreads - 1) / kThreads;
+  const long long ntiles = tiles_per_b * B;
+  const int per_k = Ci + 1 + Co;             // sums per hidden unit
+  for (long long tile = blockIdx.x; tile < ntiles; tile += gridDim.x) {
+    const long long b = tile / tiles_per_b;
+    const long long p = (tile % tiles_per_b) * kThreads + tid;
+    const bool live = p < N;
+    float xr[CI], gxr[CI], gr[4];
+#pragma unroll
+    for (int i = 0; i < CI; ++i) {
+      xr[i] = (live && i < Ci) ? x[(b * Ci + i) * N + p] : 0.f;
+      gxr[i] = 0.f;
+      if (i < Ci) XS[i * sR + tid] = xr[i];
+    }
+#pragma unroll
+    for (int o = 0; o < 4; ++o) {
+      gr[o] = (live && o < Co) ? g[(b * Co + o) * N + p] : 0.f;
+      if (o < Co) GS[o * sR + tid] = gr[o];
+    }
+    for (int k0 = 0; k0 < H; k0 += kMlpChunk) {
+      __syncthreads();                         // the previous chunk's pair sums have read GH, AA
+      for (int kk = 0; kk < kMlpChunk; ++kk) {
+        const int k = k0 + kk;
+        float ghv = 0.f, av = 0.f;
+        if (k < H) {
+          float h = b1 != nullptr ? b1[k] : 0.f;
+#pragma unroll
+          for (int i = 0; i < CI; ++i)
+            if (i < Ci) h = fmaf(W1[k * Ci + i], xr[i], h);
+          float t = 0.f;
+#pragma unroll
+          for (int o = 0; o < 4; ++o)
+            if (o < Co) t = fmaf(W2[o * H + k], gr[o], t);
+          av = gelu_f(h);
+          ghv = t * gelu_prime_f(h);
+#pragma unroll
+          for (int i = 0; i < CI; ++i)
+            if (i < Ci) gxr[i] = fmaf(W1[k * Ci + i], ghv, gxr[i]);
+        }
+        GH[kk * sR + tid] = ghv;
+        AA[kk * sR + tid] = av;
+      }
+      __syncthreads();
+      for (int q = tid; q < kMlpChunk * per_k; q += kThreads) {
+        const int kk = q / per_k, r = q - kk * per_k;
+        const int k = k0 + kk;
+        if (k >= H) continue;
+        const float* u = r <= Ci ? GH + kk * sR : GS + (r - Ci - 1) * sR;
+        float sum = 0.f;
+        int dst;
+        if (r < Ci) {
+          const float* w = XS + r * sR;
+          for (int t = 0; t < kThreads; ++t) sum = fmaf(u[t], w[t], sum);
+          dst = k * Ci + r;
+        } else if (r == Ci) {
+          for (int t = 0; t < kThreads; ++t) sum += u[t];
+          dst = H * Ci + k;
+        } else {
+          const float* w = AA + kk * sR;
+          for (int t = 0; t < kThreads; ++t) sum = fmaf(u[t], w[t], sum);
+          dst = H * (Ci + 1) + (r - Ci - 1) * H + k;
+        }
+        ACC[dst] += (double)sum;
+      }
+    }
+    // gb2[o] = sum g_o
+    if (tid < Co) {
+      const float* u = GS + tid * sR;
+      float sum = 0.f;
+      for (int t = 0; t < kThreads; ++t) sum += u[t];
+      ACC[H * (Ci + 1) + Co * H + tid] += (double)sum;
+    }
+    if (gx != nullptr && live) {
+#pragma unroll
+      for (int i = 0; i < CI; ++i)
+        if (i < Ci) gx[(b * Ci + i) * N + p] = gxr[i];
+    }
+    __syncthreads();                           // XS, GS are rewritten by the next tile
+  }
+  __syncthreads();
+  for (int q = tid; q < nsum; q += kThreads) part[(long long)blockIdx.x * nsum + q] = ACC[q];
 }
 
 // ------------------------------------------------------------------------------------------
@@ -2073,6 +2206,60 @@ hipError_t launch_adam(int64_t n, float* p, const float* g, float* m, float* v, 
   if (nb > 65536) nb = 65536;
   hipLaunchKernelGGL(adam_kernel, dim3((unsigned)nb), dim3(kThreads), 0, s, (long long)n, p, g, m, v, (float)lr,
                      (float)beta1, (float)(1.0 - beta1), (float)beta2, (float)(1.0 - beta2), (float)eps, c1, c2);
+  return hipGetLastError();
+}
+
+// doubles of partial sums + floats of a transposed weight
+size_t pointwise_bwd_workspace_bytes(int Ci, int H, int Co) {
+  const size_t lin = (size_t)2048 * ((size_t)Co * Ci + Co) * 8 + (size_t)Co * Ci * 4 + 64;
+  const size_t mlp = (size_t)kMlpBlocks * ((size_t)H * (Ci + 1) + (size_t)Co * H + Co) * 8 + 64;
+  return lin > mlp ? lin : mlp;
+}
+
+hipError_t launch_pointwise_linear_bwd(int B, int Ci, int Co, int64_t N, const float* x, const float* W,
+                                       const float* g, float* gx, float* gW, float* gb, void* ws,
+                                       hipStream_t s) {
+  if (Co * Ci + Co > kBwdPairs * kThreads || Ci > 32) return hipErrorInvalidValue;
+  if (N <= 0) return hipErrorInvalidValue;
+  double* part = static_cast<double*>(ws);
+  const int64_t tiles = (int64_t)B * ((N + kBwdTile - 1) / kBwdTile);
+  const int nblk = (int)(tiles < 2048 ? tiles : 2048);
+  if (gW != nullptr || gb != nullptr) {
+    const size_t lds = (size_t)(Co + Ci) * (kBwdTile + 1) * 4;
+    hipLaunchKernelGGL(bwd_pointwise_kernel, dim3((unsigned)nblk), dim3(kThreads), lds, s, g, g, x,
+                       (float*)nullptr, part, B, Ci, Co, (long long)N, 0, 0, 0.f);
+    hipLaunchKernelGGL(reduce_partials_kernel, dim3((Co * Ci + Co + 63) / 64), dim3(64 * kRedGroups), 0, s,
+                       part, nblk, Co, Ci, gW, gb);
+  }
+  if (gx != nullptr) {
+    float* wt = reinterpret_cast<float*>(part + (size_t)2048 * (Co * Ci + Co));
+    hipLaunchKernelGGL(transpose_kernel, dim3((Co * Ci + 255) / 256), dim3(256), 0, s, W, wt, Co, Ci);
+    const hipError_t e = launch_pointwise_linear(B, Co, Ci, N, g, wt, nullptr, gx, s);
+    if (e != hipSuccess) return e;
+  }
+  return hipGetLastError();
+}
+
+hipError_t launch_pointwise_mlp2_bwd(int B, int Ci, int H, int Co, int64_t N, const float* x, const float* W1,
+                                     const float* b1, const float* W2, const float* g, float* gx, float* gW1,
+                                     float* gb1, float* gW2, float* gb2, void* ws, hipStream_t s) {
+  if (Ci > 32 || Co > 4 || N <= 0) return hipErrorInvalidValue;
+  const int nsum = H * (Ci + 1) + Co * H + Co;
+  size_t lds_floats = (size_t)(Ci + Co + 2 * kMlpChunk) * (kThreads + 1);
+  lds_floats += lds_floats & 1;
+  const size_t lds = lds_floats * 4 + (size_t)nsum * 8;
+  if (lds > (size_t)(150 * 1024)) return hipErrorInvalidValue;
+  const int64_t tiles = (int64_t)B * ((N + kThreads - 1) / kThreads);
+  const int nblk = (int)(tiles < kMlpBlocks ? tiles : kMlpBlocks);
+  double* part = static_cast<double*>(ws);
+  if (Ci <= 20)
+    hipLaunchKernelGGL((mlp2_bwd_kernel<20>), dim3((unsigned)nblk), dim3(kThreads), lds, s, B, Ci, H, Co,
+                       (long long)N, x, W1, b1, W2, g, gx, part);
+  else
+    hipLaunchKernelGGL((mlp2_bwd_kernel<32>), dim3((unsigned)nblk), dim3(kThreads), lds, s, B, Ci, H, Co,
+                       (long long)N, x, W1, b1, W2, g, gx, part);
+  hipLaunchKernelGGL(reduce_ranges_kernel, dim3((nsum + kThreads - 1) / kThreads), dim3(kThreads), 0, s, part,
+                     nblk, H * Ci, H, Co * H, Co, gW1, gb1, gW2, gb2);
   return hipGetLastError();
 }
 

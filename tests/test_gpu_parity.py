@@ -369,3 +369,51 @@ def test_adam_steps_match_oracle_for_real_and_complex_parameters():
             assert rel(host(p), po) <= TOL
             # the update itself, not only the updated parameter
             assert rel(host(p).astype(np.float64) - before, po - before) <= 1e-3
+
+
+@pytest.mark.parametrize("shape", [
+    # batch, c_in, hidden, c_out, points
+    (2, 3, 5, 2, 77),                 # ragged tile, hidden below one chunk
+    (1, 20, 128, 1, 3000),            # the projection of the benchmark network, several tiles
+    (2, 5, 20, 4, 1024),              # whole tiles, four outputs
+])
+def test_pointwise_adjoints_match_oracle(shape):
+    batch, c_in, hidden, c_out, npts = shape
+    rng = np.random.default_rng([19, c_in, hidden, c_out, npts])
+    grid = (npts, 1, 1, 1)
+    x = rng.standard_normal((batch, c_in) + grid).astype(np.float32)
+    w1 = (rng.standard_normal((hidden, c_in)) / np.sqrt(c_in)).astype(np.float32)
+    b1 = (0.1 * rng.standard_normal(hidden)).astype(np.float32)
+    w2 = (rng.standard_normal((c_out, hidden)) / np.sqrt(hidden)).astype(np.float32)
+    gu = rng.standard_normal((batch, c_out) + grid).astype(np.float32)
+    nbytes = max(B.fno_pointwise_bwd_workspace_bytes(c_in, hidden, c_out),
+                 B.fno_pointwise_bwd_workspace_bytes(c_in, 0, min(hidden, 32)))
+    ws = torch.empty(nbytes // 4 + 2, dtype=torch.float32, device="cuda")
+    # the linear map (lift): hidden plays the output width
+    gh_in = rng.standard_normal((batch, hidden) + grid).astype(np.float32)
+    gx = torch.empty((batch, c_in) + grid, device="cuda")
+    gW = torch.empty((hidden, c_in), device="cuda")
+    gb = torch.empty(hidden, device="cuda")
+    if hidden <= 32:
+        B.fno_pointwise_linear_bwd(batch, c_in, hidden, npts, dev(x), dev(w1), dev(gh_in), gx, gW, gb, ws)
+        torch.cuda.synchronize()
+        want = O.pointwise_linear_bwd(x, w1, gh_in)
+        assert rel(host(gx), want["gx"]) <= TOL and rel(host(gW), want["gW"]) <= TOL
+        assert rel(host(gb), want["gb"]) <= TOL
+    # the two-layer projection
+    gW1 = torch.empty((hidden, c_in), device="cuda")
+    gb1 = torch.empty(hidden, device="cuda")
+    gW2 = torch.empty((c_out, hidden), device="cuda")
+    gb2 = torch.empty(c_out, device="cuda")
+    B.fno_pointwise_mlp2_bwd(batch, c_in, hidden, c_out, npts, dev(x), dev(w1), dev(b1), dev(w2), dev(gu),
+                             gx, gW1, gb1, gW2, gb2, ws)
+    torch.cuda.synchronize()
+    want = O.pointwise_mlp2_bwd(x, w1, b1, w2, gu)
+    for name, got in (("gx", gx), ("gW1", gW1), ("gb1", gb1), ("gW2", gW2), ("gb2", gb2)):
+        assert rel(host(got), want[name]) <= TOL, name
+    # identical bits on a second run
+    gW1b, gW2b = torch.empty_like(gW1), torch.empty_like(gW2)
+    B.fno_pointwise_mlp2_bwd(batch, c_in, hidden, c_out, npts, dev(x), dev(w1), dev(b1), dev(w2), dev(gu),
+                             None, gW1b, None, gW2b, None, ws)
+    torch.cuda.synchronize()
+    assert torch.equal(gW1, gW1b) and torch.equal(gW2, gW2b)
