@@ -417,3 +417,91 @@ def test_pointwise_adjoints_match_oracle(shape):
                              None, gW1b, None, gW2b, None, ws)
     torch.cuda.synchronize()
     assert torch.equal(gW1, gW1b) and torch.equal(gW2, gW2b)
+
+
+def test_whole_network_training_step_matches_oracle():
+    """Lift, two blocks, projection; relative L2 loss; backward through all of it; one Adam step.
+
+    Every stage runs through the C ABI; the float64 oracle differentiates its own forward."""
+    grid, modes, c_in, width, hidden, nblocks = (8, 8, 8, 8), (2, 2, 2, 3), 3, 8, 16, 2
+    spec = O.LayerSpec(grid, modes, 0)
+    counts = tuple(len(k) for k in O.mode_lists(spec))
+    npts = int(np.prod(grid))
+    a = synth.normal_field(0, synth.T_X, 1, c_in, grid)
+    y = synth.normal_field(1, synth.T_TARGET, 1, 1, grid)
+    lw, lb = synth.linear_weights(0, width, c_in, synth.T_LIFT), synth.bias(0, width, synth.T_LIFT)
+    blocks = [(synth.spectral_weights(k, width, width, counts), synth.linear_weights(10 + k, width, width),
+               synth.bias(10 + k, width)) for k in range(nblocks)]
+    w1, b1 = synth.linear_weights(1, hidden, width, synth.T_PROJ), synth.bias(1, hidden, synth.T_PROJ)
+    w2, b2 = synth.linear_weights(2, 1, hidden, synth.T_PROJ), synth.bias(2, 1, synth.T_PROJ)
+
+    # ---- GPU: forward
+    desc = B.make_desc(1, width, width, grid, modes, 0, B.FNO_ACT_GELU)
+    ws = B.alloc_workspace(desc, B.FNO_OP_BLOCK_BWD)
+    d = {k: dev(v) for k, v in dict(a=a, y=y, lw=lw, lb=lb, w1=w1, b1=b1, w2=w2, b2=b2).items()}
+    dblocks = [tuple(dev(t) for t in blk) for blk in blocks]
+    vs = [torch.empty((1, width) + grid, device="cuda")]
+    B.fno_pointwise_linear(1, c_in, width, npts, d["a"], d["lw"], d["lb"], vs[0])
+    zs, xhs = [], []
+    for (R, W, b) in dblocks:
+        out = torch.empty_like(vs[0])
+        z = torch.empty_like(vs[0])
+        xh = torch.empty((1, width) + counts, dtype=torch.complex64, device="cuda")
+        B.fno_block_fwd(desc, vs[-1], R, W, b, out, z, xh, ws)
+        vs.append(out); zs.append(z); xhs.append(xh)
+    u = torch.empty((1, 1) + grid, device="cuda")
+    B.fno_pointwise_mlp2(1, width, hidden, 1, npts, vs[-1], d["w1"], d["b1"], d["w2"], d["b2"], u)
+    # ---- loss and its gradient
+    lws = torch.empty(B.fno_rel_l2_workspace_bytes() // 4, dtype=torch.float32, device="cuda")
+    loss = torch.empty(1, device="cuda")
+    gu = torch.empty_like(u)
+    B.fno_rel_l2_loss(npts, u, d["y"], loss, gu, lws)
+    # ---- backward
+    pws = torch.empty(max(B.fno_pointwise_bwd_workspace_bytes(width, hidden, 1),
+                          B.fno_pointwise_bwd_workspace_bytes(c_in, 0, width)) // 4 + 2,
+                      dtype=torch.float32, device="cuda")
+    gv = torch.empty_like(vs[0])
+    g = {"w1": torch.empty_like(d["w1"]), "b1": torch.empty_like(d["b1"]), "w2": torch.empty_like(d["w2"]),
+         "b2": torch.empty_like(d["b2"]), "lw": torch.empty_like(d["lw"]), "lb": torch.empty_like(d["lb"])}
+    B.fno_pointwise_mlp2_bwd(1, width, hidden, 1, npts, vs[-1], d["w1"], d["b1"], d["w2"], gu, gv,
+                             g["w1"], g["b1"], g["w2"], g["b2"], pws)
+    gblocks = [None] * nblocks
+    for k in reversed(range(nblocks)):
+        R, W, b = dblocks[k]
+        gx = torch.empty_like(vs[0])
+        gR, gW, gb = torch.empty_like(R), torch.empty_like(W), torch.empty_like(b)
+        B.fno_block_bwd(desc, vs[k], R, W, zs[k], xhs[k], gv, gx, gR, gW, gb, ws)
+        gblocks[k] = (gR, gW, gb)
+        gv = gx
+    B.fno_pointwise_linear_bwd(1, c_in, width, npts, d["a"], d["lw"], gv, None, g["lw"], g["lb"], pws)
+    torch.cuda.synchronize()
+
+    # ---- oracle
+    uo = O.fno_forward(a, lw, lb, blocks, (w1, b1, w2, b2), spec)
+    assert rel(host(u), uo) <= TOL
+    assert abs(float(loss.cpu()) - O.rel_l2_loss(uo, y)) <= TOL * O.rel_l2_loss(uo, y)
+    ref = O.fno_backward(a, lw, lb, blocks, (w1, b1, w2, b2), spec, O.rel_l2_grad(uo, y))
+    GT = 5 * TOL     # gradients pass through 2 blocks and 3 pointwise stages
+    assert rel(host(g["w1"]), ref["proj"]["gW1"]) <= GT and rel(host(g["b1"]), ref["proj"]["gb1"]) <= GT
+    assert rel(host(g["w2"]), ref["proj"]["gW2"]) <= GT and rel(host(g["b2"]), ref["proj"]["gb2"]) <= GT
+    for k in range(nblocks):
+        gR, gW, gb = gblocks[k]
+        assert rel(host(gR), ref["blocks"][k]["gR"]) <= GT, k
+        assert rel(host(gW), ref["blocks"][k]["gW"]) <= GT, k
+        assert rel(host(gb), ref["blocks"][k]["gb"]) <= GT, k
+    assert rel(host(g["lw"]), ref["lift"]["gW"]) <= GT and rel(host(g["lb"]), ref["lift"]["gb"]) <= GT
+
+    # ---- one Adam step on every parameter (complex weights as pairs of floats)
+    params = [(d["lw"], g["lw"], lw, ref["lift"]["gW"]), (d["w1"], g["w1"], w1, ref["proj"]["gW1"])]
+    R0 = dblocks[0][0]
+    params.append((torch.view_as_real(R0).reshape(-1), torch.view_as_real(gblocks[0][0]).reshape(-1),
+                   np.ascontiguousarray(blocks[0][0]).view(np.float32).ravel(),
+                   np.ascontiguousarray(ref["blocks"][0]["gR"].astype(np.complex128)).view(np.float64).ravel()))
+    for p, grad, p_host, g_ref in params:
+        n = p.numel()
+        m = torch.zeros(n, device="cuda")
+        v = torch.zeros(n, device="cuda")
+        B.fno_adam_step(n, p, grad, m, v, 1e-3, 0.9, 0.999, 1e-8, 1)
+        torch.cuda.synchronize()
+        po, _, _ = O.adam_step(p_host.astype(np.float64).ravel(), np.asarray(g_ref).ravel(), np.zeros(n), np.zeros(n), 1)
+        assert rel(host(p).ravel(), po) <= TOL
