@@ -28,6 +28,9 @@ def parse():
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--config", default="cfg4", help="workload name from synth.CONFIGS (block forward; cfg5: forward + backward), or time_lift")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--network", action="store_true",
+                    help="time one training step of the whole network of the workload (cfg3: lift, blocks, "
+                         "projection, relative L2 loss, backward, Adam) instead of one block")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="only run plain device copies of 4 GiB (reference reading for rocprofv3 --pmc "
                          "FETCH_SIZE / WRITE_SIZE), then exit")
@@ -109,6 +112,86 @@ def time_lift_bench(args, torch, B):
     }))
 
 
+def network_step_bench(args, torch, B, synth):
+    """One training step of a whole network: every stage through the C ABI, all tensors resident."""
+    cfg = synth.CONFIGS[args.config]
+    batch, width, grid, modes = cfg["batch"], cfg["width"], tuple(cfg["grid"]), tuple(cfg["modes"])
+    c_in, hidden, nblocks = cfg.get("in_channels", 5), cfg.get("hidden", 128), cfg.get("blocks", 4)
+    counts = synth.retained_counts(modes)
+    npts = 1
+    for n in grid:
+        npts *= n
+    torch.cuda.set_device(0)
+    gen = torch.Generator(device="cuda")
+    gen.manual_seed(0)
+    rn = lambda *shape: torch.randn(shape, device="cuda", generator=gen)
+    a, y = rn(batch, c_in, *grid), rn(batch, 1, *grid)
+    lw, lb = rn(width, c_in) / c_in ** 0.5, 0.1 * rn(width)
+    blocks = [(torch.view_as_complex(rn(width, width, *counts, 2) / width), rn(width, width) / width ** 0.5,
+               0.1 * rn(width)) for _ in range(nblocks)]
+    w1, b1, w2, b2 = rn(hidden, width) / width ** 0.5, 0.1 * rn(hidden), rn(1, hidden) / hidden ** 0.5, 0.1 * rn(1)
+    desc = B.make_desc(batch, width, width, grid, modes, 0, B.FNO_ACT_GELU)
+    ws = B.alloc_workspace(desc, B.FNO_OP_BLOCK_BWD)
+    act = lambda: torch.empty((batch, width) + grid, device="cuda")
+    vs = [act() for _ in range(nblocks + 1)]
+    zs = [act() for _ in range(nblocks)]
+    xhs = [torch.empty((batch, width) + counts, dtype=torch.complex64, device="cuda") for _ in range(nblocks)]
+    u, gu = torch.empty_like(y), torch.empty_like(y)
+    gva, gvb = act(), act()
+    lws = torch.empty(B.fno_rel_l2_workspace_bytes() // 4, dtype=torch.float32, device="cuda")
+    pws = torch.empty(max(B.fno_pointwise_bwd_workspace_bytes(width, hidden, 1),
+                          B.fno_pointwise_bwd_workspace_bytes(c_in, 0, width)) // 4 + 2,
+                      dtype=torch.float32, device="cuda")
+    loss = torch.empty(1, device="cuda")
+    params = [lw, lb, w1, b1, w2, b2] + [t for blk in blocks for t in blk]
+    flat = [torch.view_as_real(p).reshape(-1) if p.is_complex() else p.reshape(-1) for p in params]
+    grads = [torch.empty_like(p) for p in params]
+    gflat = [torch.view_as_real(t).reshape(-1) if t.is_complex() else t.reshape(-1) for t in grads]
+    moms = [(torch.zeros_like(f), torch.zeros_like(f)) for f in flat]
+    glw, glb, gw1, gb1, gw2, gb2 = grads[:6]
+    gblk = [tuple(grads[6 + 3 * k: 9 + 3 * k]) for k in range(nblocks)]
+    state = {"step": 0}
+
+    def step():
+        state["step"] += 1
+        B.fno_pointwise_linear(batch, c_in, width, npts, a, lw, lb, vs[0])
+        for k, (R, W, b) in enumerate(blocks):
+            B.fno_block_fwd(desc, vs[k], R, W, b, vs[k + 1], zs[k], xhs[k], ws)
+        B.fno_pointwise_mlp2(batch, width, hidden, 1, npts, vs[-1], w1, b1, w2, b2, u)
+        B.fno_rel_l2_loss(u.numel(), u, y, loss, gu, lws)
+        B.fno_pointwise_mlp2_bwd(batch, width, hidden, 1, npts, vs[-1], w1, b1, w2, gu, gva, gw1, gb1, gw2, gb2, pws)
+        gin, gout = gva, gvb
+        for k in reversed(range(nblocks)):
+            R, W, b = blocks[k]
+            B.fno_block_bwd(desc, vs[k], R, W, zs[k], xhs[k], gin, gout, gblk[k][0], gblk[k][1], gblk[k][2], ws)
+            gin, gout = gout, gin
+        B.fno_pointwise_linear_bwd(batch, c_in, width, npts, a, lw, gin, None, glw, glb, pws)
+        for f, gf, (m, v) in zip(flat, gflat, moms):
+            B.fno_adam_step(f.numel(), f, gf, m, v, 1e-3, 0.9, 0.999, 1e-8, state["step"])
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    ms = 1e3 * (time.perf_counter() - t0) / args.steps
+    pc = float(batch) * width * npts
+    print(json.dumps({
+        "metric": "FNO spectral layer Gpoint-channels/s + achieved HBM GB/s on 1 MI355X",
+        "value": nblocks * pc / (ms * 1e-3) / 1e9, "unit": "Gpoint-channels/s", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": ms, "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+        "config": {"workload": f"{args.config} network training step: lift {c_in}->{width}, {nblocks} blocks, projection "
+                               f"{width}->{hidden}->1, relative L2 loss, backward, Adam; batch {batch}, grid "
+                               f"{grid[0]}x{grid[1]}x{grid[2]}x{grid[3]}; value counts the point-channels of the "
+                               f"{nblocks} blocks once per step",
+                   "global_batch": batch, "parallelism": "single GPU"},
+        "loss": float(loss.cpu()),
+    }))
+
+
 def main():
     args = parse()
     if args.gpus != 1:
@@ -130,6 +213,9 @@ def main():
         return
     if args.config == "time_lift":
         time_lift_bench(args, torch, B)
+        return
+    if args.network:
+        network_step_bench(args, torch, B, synth)
         return
     cfg = synth.CONFIGS[args.config]
     batch, width, grid, modes = cfg["batch"], cfg["width"], tuple(cfg["grid"]), tuple(cfg["modes"])

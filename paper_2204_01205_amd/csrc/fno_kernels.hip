@@ -1555,6 +1555,300 @@ __global__ __launch_bounds__(kThreads) void mlp2_bwd_kernel(
 }
 
 // ------------------------------------------------------------------------------------------
+// The two-layer projection and its adjoint on the matrix cores
+// ------------------------------------------------------------------------------------------
+// v_mfma_f32_32x32x2 adds A (32x2) times B (2x32) to a 32x32 accumulator in full fp32.  Lane l
+// supplies A[l%32][l/32] and B[l/32][l%32]; register v of its accumulator holds the element in
+// row mfma_row(v, l/32), column l%32.
+//
+// A block of H/32 waves walks over tiles of 64 points (two column blocks of 32); wave w owns the
+// hidden units 32w .. 32w+31 and keeps their weights in registers, already in operand order.
+//   h   = [W1 | b1] [x ; 1]      K runs over the input channels and a row of ones
+//   gx  = W1^T gh                K runs over the wave's hidden units in accumulator order, so
+//                                the registers that hold gh are the B operand as they stand
+//   gW1 | gb1 = gh [x ; 1]^T     K runs over the points; gh goes through LDS to turn it
+// The activation, its slope and the products with W2 are the vector units' share.
+typedef float v16f __attribute__((ext_vector_type(16)));
+__device__ __forceinline__ int mfma_row(int v, int half) { return 8 * (v >> 2) + 4 * half + (v & 3); }
+
+constexpr int kMlpTile = 64;             // points per pass of a block
+constexpr int kMlpStage = 6;             // values a thread stages per pass
+constexpr int kMlpXS = kMlpTile + 1;     // row stride of the staged tile (odd: column reads spread over the banks)
+constexpr int kMlpTS = 33;               // row stride of a wave's 32x32 turn buffer
+constexpr int kMlpFlush = 16;            // passes between flushes of the fp32 weight-gradient accumulator
+
+// gelu(z) and its derivative Phi(z) + z phi(z), with the branch-free erf of gelu_fast_f
+__device__ __forceinline__ void gelu_and_slope(float z, float& a, float& d) {
+  const float az = fabsf(z);
+  const float x = az * 0.70710678118654752440f;
+  float p = fmaf(x, 0.0000430638f, 0.0002765672f);
+  p = fmaf(x, p, 0.0001520143f);
+  p = fmaf(x, p, 0.0092705272f);
+  p = fmaf(x, p, 0.0422820123f);
+  p = fmaf(x, p, 0.0705230784f);
+  p = fmaf(x, p, 1.0f);
+  p = p * p; p = p * p; p = p * p; p = p * p;
+  const float erfx = 1.0f - __builtin_amdgcn_rcpf(p);
+  a = 0.5f * fmaf(az, erfx, z);
+  const float cdf = fmaf(0.5f, copysignf(erfx, z), 0.5f);
+  const float pdf = 0.39894228040143267794f * __expf(-0.5f * z * z);
+  d = fmaf(z, pdf, cdf);
+}
+
+template <int KS, int CO>
+__global__ __launch_bounds__(512) void mlp2_fwd_mfma_kernel(
+    int B, int Ci, int H, int Co, long long N, const float* __restrict__ x, const float* __restrict__ W1,
+    const float* __restrict__ b1, const float* __restrict__ W2, const float* __restrict__ b2,
+    float* __restrict__ y) {
+  HIP_DYNAMIC_SHARED(float, smem)
+  const int nthreads = blockDim.x, nw = nthreads >> 6;
+  const int tid = threadIdx.x, w = tid >> 6, lane = tid & 63, half = lane >> 5, c = lane & 31;
+  float* XS = smem;                          // [32][kMlpXS]: rows < Ci the tile, row Ci ones, the rest zero
+  float* YP = XS + 32 * kMlpXS;              // [nw][CO][kMlpTile] partial outputs of the waves
+  for (int e = tid; e < (32 - Ci) * kMlpXS; e += nthreads) XS[Ci * kMlpXS + e] = e < kMlpXS ? 1.f : 0.f;
+  float A1[KS], W2r[CO][16];
+#pragma unroll
+  for (int s = 0; s < KS; ++s) {
+    const int i = 2 * s + half, k = w * 32 + c;
+    A1[s] = i < Ci ? W1[k * Ci + i] : ((i == Ci && b1 != nullptr) ? b1[k] : 0.f);
+  }
+#pragma unroll
+  for (int o = 0; o < CO; ++o)
+#pragma unroll
+    for (int v = 0; v < 16; ++v) W2r[o][v] = o < Co ? W2[o * H + w * 32 + mfma_row(v, half)] : 0.f;
+  const long long tiles_per_b = (N + kMlpTile - 1) / kMlpTile;
+  const long long ntiles = tiles_per_b * B;
+  const int nstage = Ci * kMlpTile;
+  float pf[kMlpStage];
+  {
+    const long long t = blockIdx.x;
+    const long long b = t / tiles_per_b, p0 = (t - b * tiles_per_b) * kMlpTile;
+#pragma unroll
+    for (int r = 0; r < kMlpStage; ++r) {
+      const int e = tid + r * nthreads, row = e >> 6, col = e & 63;
+      pf[r] = (t < ntiles && e < nstage && p0 + col < N) ? x[(b * Ci + row) * N + p0 + col] : 0.f;
+    }
+  }
+  for (long long t = blockIdx.x; t < ntiles; t += gridDim.x) {
+#pragma unroll
+    for (int r = 0; r < kMlpStage; ++r) {
+      const int e = tid + r * nthreads, row = e >> 6, col = e & 63;
+      if (e < nstage) XS[row * kMlpXS + col] = pf[r];
+    }
+    __syncthreads();
+    {
+      const long long tn = t + gridDim.x;
+      const long long b = tn / tiles_per_b, p0 = (tn - b * tiles_per_b) * kMlpTile;
+#pragma unroll
+      for (int r = 0; r < kMlpStage; ++r) {
+        const int e = tid + r * nthreads, row = e >> 6, col = e & 63;
+        pf[r] = (tn < ntiles && e < nstage && p0 + col < N) ? x[(b * Ci + row) * N + p0 + col] : 0.f;
+      }
+    }
+    const long long b = t / tiles_per_b, p0 = (t - b * tiles_per_b) * kMlpTile;
+#pragma unroll
+    for (int nb = 0; nb < 2; ++nb) {
+      const int pc = nb * 32 + c;
+      v16f hacc = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+      for (int s = 0; s < KS; ++s)
+        hacc = __builtin_amdgcn_mfma_f32_32x32x2f32(A1[s], XS[(2 * s + half) * kMlpXS + pc], hacc, 0, 0, 0);
+      float yp[CO];
+#pragma unroll
+      for (int o = 0; o < CO; ++o) yp[o] = 0.f;
+#pragma unroll
+      for (int v = 0; v < 16; ++v) {
+        const float a = gelu_fast_f(hacc[v]);
+#pragma unroll
+        for (int o = 0; o < CO; ++o) yp[o] = fmaf(W2r[o][v], a, yp[o]);
+      }
+#pragma unroll
+      for (int o = 0; o < CO; ++o) {
+        yp[o] += __shfl_xor(yp[o], 32);
+        if (half == 0) YP[(w * CO + o) * kMlpTile + pc] = yp[o];
+      }
+    }
+    __syncthreads();
+    for (int e = tid; e < Co * kMlpTile; e += nthreads) {
+      const int o = e >> 6, col = e & 63;
+      float sum = b2 != nullptr ? b2[o] : 0.f;
+      for (int ww = 0; ww < nw; ++ww) sum += YP[(ww * CO + o) * kMlpTile + col];
+      if (p0 + col < N) y[(b * Co + o) * N + p0 + col] = sum;
+    }
+  }
+}
+
+template <int KS, int CO>
+__global__ __launch_bounds__(512) void mlp2_bwd_mfma_kernel(
+    int B, int Ci, int H, int Co, long long N, const float* __restrict__ x, const float* __restrict__ W1,
+    const float* __restrict__ b1, const float* __restrict__ W2, const float* __restrict__ g,
+    float* __restrict__ gx, double* __restrict__ part) {
+  HIP_DYNAMIC_SHARED(float, smem)
+  const int nthreads = blockDim.x, nw = nthreads >> 6;
+  const int tid = threadIdx.x, w = tid >> 6, lane = tid & 63, half = lane >> 5, c = lane & 31;
+  float* XS = smem;                                      // [32][kMlpXS]: tile, ones, zeros as above
+  float* GS = XS + 32 * kMlpXS;                          // [CO][kMlpTile] upstream gradient of the tile
+  float* T = GS + CO * kMlpTile + w * (32 * kMlpTS);     // this wave's [32][kMlpTS] turn buffer
+  float* GXP = GS + CO * kMlpTile + nw * (32 * kMlpTS);  // [nw][Ci][kMlpXS] partial gx of the waves
+  int acc_off = 32 * kMlpXS + CO * kMlpTile + nw * (32 * kMlpTS) + nw * Ci * kMlpXS;
+  acc_off += acc_off & 1;
+  double* ACC = reinterpret_cast<double*>(smem + acc_off);   // [nsum] gW1 | gb1 | gW2 | gb2
+  const int nsum = H * (Ci + 1) + Co * H + Co;
+  for (int q = tid; q < nsum; q += nthreads) ACC[q] = 0.0;
+  for (int e = tid; e < (32 - Ci) * kMlpXS; e += nthreads) XS[Ci * kMlpXS + e] = e < kMlpXS ? 1.f : 0.f;
+  float A1[KS], A2[16], W2r[CO][16];
+#pragma unroll
+  for (int s = 0; s < KS; ++s) {
+    const int i = 2 * s + half, k = w * 32 + c;
+    A1[s] = i < Ci ? W1[k * Ci + i] : ((i == Ci && b1 != nullptr) ? b1[k] : 0.f);
+  }
+#pragma unroll
+  for (int v = 0; v < 16; ++v) {
+    const int k = w * 32 + mfma_row(v, half);
+    A2[v] = c < Ci ? W1[k * Ci + c] : 0.f;
+#pragma unroll
+    for (int o = 0; o < CO; ++o) W2r[o][v] = o < Co ? W2[o * H + k] : 0.f;
+  }
+  const long long tiles_per_b = (N + kMlpTile - 1) / kMlpTile;
+  const long long ntiles = tiles_per_b * B;
+  const int nstage = (Ci + Co) * kMlpTile;
+  v16f accw = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+  float acc2[CO][16], accg[CO];
+#pragma unroll
+  for (int o = 0; o < CO; ++o) {
+    accg[o] = 0.f;
+#pragma unroll
+    for (int v = 0; v < 16; ++v) acc2[o][v] = 0.f;
+  }
+  float pf[kMlpStage];
+  {
+    const long long t = blockIdx.x;
+    const long long b = t / tiles_per_b, p0 = (t - b * tiles_per_b) * kMlpTile;
+#pragma unroll
+    for (int r = 0; r < kMlpStage; ++r) {
+      const int e = tid + r * nthreads, row = e >> 6, col = e & 63;
+      float val = 0.f;
+      if (t < ntiles && e < nstage && p0 + col < N)
+        val = row < Ci ? x[(b * Ci + row) * N + p0 + col] : g[(b * Co + (row - Ci)) * N + p0 + col];
+      pf[r] = val;
+    }
+  }
+  int pass = 0;
+  for (long long t = blockIdx.x; t < ntiles; t += gridDim.x) {
+#pragma unroll
+    for (int r = 0; r < kMlpStage; ++r) {
+      const int e = tid + r * nthreads, row = e >> 6, col = e & 63;
+      if (e < nstage) {
+        if (row < Ci) XS[row * kMlpXS + col] = pf[r];
+        else GS[(row - Ci) * kMlpTile + col] = pf[r];
+      }
+    }
+    __syncthreads();
+    {
+      const long long tn = t + gridDim.x;
+      const long long b = tn / tiles_per_b, p0 = (tn - b * tiles_per_b) * kMlpTile;
+#pragma unroll
+      for (int r = 0; r < kMlpStage; ++r) {
+        const int e = tid + r * nthreads, row = e >> 6, col = e & 63;
+        float val = 0.f;
+        if (tn < ntiles && e < nstage && p0 + col < N)
+          val = row < Ci ? x[(b * Ci + row) * N + p0 + col] : g[(b * Co + (row - Ci)) * N + p0 + col];
+        pf[r] = val;
+      }
+    }
+    const long long b = t / tiles_per_b, p0 = (t - b * tiles_per_b) * kMlpTile;
+#pragma unroll 1
+    for (int nb = 0; nb < 2; ++nb) {
+      const int pc = nb * 32 + c;
+      v16f hacc = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+      for (int s = 0; s < KS; ++s)
+        hacc = __builtin_amdgcn_mfma_f32_32x32x2f32(A1[s], XS[(2 * s + half) * kMlpXS + pc], hacc, 0, 0, 0);
+      float gl[CO];
+#pragma unroll
+      for (int o = 0; o < CO; ++o) {
+        gl[o] = o < Co ? GS[o * kMlpTile + pc] : 0.f;
+        if (half == 0) accg[o] += gl[o];
+      }
+      float gh[16];
+#pragma unroll
+      for (int v = 0; v < 16; ++v) {
+        float a, d;
+        gelu_and_slope(hacc[v], a, d);
+        float tt = 0.f;
+#pragma unroll
+        for (int o = 0; o < CO; ++o) {
+          tt = fmaf(W2r[o][v], gl[o], tt);
+          acc2[o][v] = fmaf(gl[o], a, acc2[o][v]);
+        }
+        gh[v] = tt * d;
+        T[mfma_row(v, half) * kMlpTS + c] = gh[v];
+      }
+      v16f gacc = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+      for (int v = 0; v < 16; ++v) gacc = __builtin_amdgcn_mfma_f32_32x32x2f32(A2[v], gh[v], gacc, 0, 0, 0);
+#pragma unroll
+      for (int v = 0; v < 16; ++v) {
+        const int row = mfma_row(v, half);
+        if (row < Ci) GXP[(w * Ci + row) * kMlpXS + pc] = gacc[v];
+      }
+      __builtin_amdgcn_wave_barrier();
+#pragma unroll
+      for (int s = 0; s < 16; ++s)
+        accw = __builtin_amdgcn_mfma_f32_32x32x2f32(T[c * kMlpTS + 2 * s + half],
+                                                    XS[c * kMlpXS + nb * 32 + 2 * s + half], accw, 0, 0, 0);
+      __builtin_amdgcn_wave_barrier();
+    }
+    __syncthreads();
+    if (gx != nullptr) {
+      for (int e = tid; e < Ci * kMlpTile; e += nthreads) {
+        const int i = e >> 6, col = e & 63;
+        float sum = 0.f;
+        for (int ww = 0; ww < nw; ++ww) sum += GXP[(ww * Ci + i) * kMlpXS + col];
+        if (p0 + col < N) gx[(b * Ci + i) * N + p0 + col] = sum;
+      }
+    }
+    if (++pass == kMlpFlush) {
+      pass = 0;
+#pragma unroll
+      for (int v = 0; v < 16; ++v) {
+        const int k = w * 32 + mfma_row(v, half);
+        if (c < Ci) ACC[k * Ci + c] += (double)accw[v];
+        else if (c == Ci) ACC[H * Ci + k] += (double)accw[v];
+        accw[v] = 0.f;
+      }
+    }
+  }
+#pragma unroll
+  for (int v = 0; v < 16; ++v) {
+    const int k = w * 32 + mfma_row(v, half);
+    if (c < Ci) ACC[k * Ci + c] += (double)accw[v];
+    else if (c == Ci) ACC[H * Ci + k] += (double)accw[v];
+  }
+  // gW2[o][k]: the lanes' sums over their points, added over the 32 lanes of a row through T
+#pragma unroll
+  for (int o = 0; o < CO; ++o) {
+    if (o < Co) {
+      __syncthreads();
+#pragma unroll
+      for (int v = 0; v < 16; ++v) T[mfma_row(v, half) * kMlpTS + c] = acc2[o][v];
+      __syncthreads();
+      if (half == 0) {
+        double sum = 0.0;
+        for (int cc = 0; cc < 32; ++cc) sum += (double)T[c * kMlpTS + cc];
+        ACC[H * (Ci + 1) + o * H + w * 32 + c] = sum;
+      }
+      float sg = accg[o];
+#pragma unroll
+      for (int m = 1; m < 64; m <<= 1) sg += __shfl_xor(sg, m);
+      if (tid == 0) ACC[H * (Ci + 1) + Co * H + o] = (double)sg;
+    }
+  }
+  __syncthreads();
+  for (int q = tid; q < nsum; q += nthreads) part[(long long)blockIdx.x * nsum + q] = ACC[q];
+}
+
+// ------------------------------------------------------------------------------------------
 // Training pieces outside the block (Sec. 4): relative L2 misfit and the Adam update
 // ------------------------------------------------------------------------------------------
 constexpr int kLossBlocks = 1024;      // partial sums of the loss (two doubles each)
@@ -2141,12 +2435,40 @@ hipError_t launch_pointwise_linear(int B, int Ci, int Co, int64_t np, const floa
   return hipGetLastError();
 }
 
+// The matrix-core projection kernels take hidden widths that are whole 32-row blocks, one wave
+// each, and tiles whose (c_in + c_out) x 64 values the block's threads stage in kMlpStage loads.
+bool mlp2_mfma_fits(int Ci, int H, int Co) {
+  if (H % 32 != 0 || H < 32 || H > 256 || Ci > 31 || Co > 4 || Ci < 1 || Co < 1) return false;
+  return Ci + Co <= kMlpStage * (H / 32);
+}
+
+size_t mlp2_bwd_mfma_lds(int Ci, int H, int Co) {
+  const int nw = H / 32, co = Co == 1 ? 1 : 4;
+  size_t floats = (size_t)32 * kMlpXS + (size_t)co * kMlpTile + (size_t)nw * 32 * kMlpTS + (size_t)nw * Ci * kMlpXS;
+  floats += floats & 1;
+  return floats * 4 + ((size_t)H * (Ci + 1) + (size_t)Co * H + Co) * 8;
+}
+
 hipError_t launch_pointwise_mlp2(int B, int Ci, int H, int Co, int64_t np, const float* x,
                                  const float* W1, const float* b1, const float* W2,
                                  const float* b2, float* y, hipStream_t s) {
   const int64_t nb = (np + kThreads - 1) / kThreads;
   if (nb > 0x7fffffffLL || B > 65535 || Co > 4 || Ci > 32) return hipErrorInvalidValue;
   if (nb == 0 || B == 0) return hipSuccess;
+  if (mlp2_mfma_fits(Ci, H, Co)) {
+    const int nw = H / 32;
+    const int64_t tiles = (int64_t)B * ((np + kMlpTile - 1) / kMlpTile);
+    const unsigned nblk = (unsigned)(tiles < 2048 ? tiles : 2048);
+    const int co = Co == 1 ? 1 : 4;
+    const size_t lds = (size_t)(32 * kMlpXS + nw * co * kMlpTile) * 4;
+#define FNO_MLPF(KSV, COV)                                                                              \
+  hipLaunchKernelGGL((mlp2_fwd_mfma_kernel<KSV, COV>), dim3(nblk), dim3(64 * nw), lds, s, B, Ci, H, Co, \
+                     (long long)np, x, W1, b1, W2, b2, y)
+    if (Ci <= 21) { if (co == 1) FNO_MLPF(11, 1); else FNO_MLPF(11, 4); }
+    else { if (co == 1) FNO_MLPF(16, 1); else FNO_MLPF(16, 4); }
+#undef FNO_MLPF
+    return hipGetLastError();
+  }
   dim3 grid((unsigned)nb, (unsigned)B);
   if (Ci <= 20)
     hipLaunchKernelGGL((pointwise_mlp2_kernel<20>), grid, dim3(kThreads), 0, s, Ci, H, Co,
@@ -2245,6 +2567,22 @@ hipError_t launch_pointwise_mlp2_bwd(int B, int Ci, int H, int Co, int64_t N, co
                                      float* gb1, float* gW2, float* gb2, void* ws, hipStream_t s) {
   if (Ci > 32 || Co > 4 || N <= 0) return hipErrorInvalidValue;
   const int nsum = H * (Ci + 1) + Co * H + Co;
+  if (mlp2_mfma_fits(Ci, H, Co) && mlp2_bwd_mfma_lds(Ci, H, Co) <= (size_t)(150 * 1024)) {
+    const int nw = H / 32, co = Co == 1 ? 1 : 4;
+    const size_t lds = mlp2_bwd_mfma_lds(Ci, H, Co);
+    const int64_t tiles = (int64_t)B * ((N + kMlpTile - 1) / kMlpTile);
+    const int nblk = (int)(tiles < kMlpBlocks ? tiles : kMlpBlocks);
+    double* part = static_cast<double*>(ws);
+#define FNO_MLPB(KSV, COV)                                                                                 \
+  hipLaunchKernelGGL((mlp2_bwd_mfma_kernel<KSV, COV>), dim3((unsigned)nblk), dim3(64 * nw), lds, s, B, Ci, \
+                     H, Co, (long long)N, x, W1, b1, W2, g, gx, part)
+    if (Ci <= 21) { if (co == 1) FNO_MLPB(11, 1); else FNO_MLPB(11, 4); }
+    else { if (co == 1) FNO_MLPB(16, 1); else FNO_MLPB(16, 4); }
+#undef FNO_MLPB
+    hipLaunchKernelGGL(reduce_ranges_kernel, dim3((nsum + kThreads - 1) / kThreads), dim3(kThreads), 0, s, part,
+                       nblk, H * Ci, H, Co * H, Co, gW1, gb1, gW2, gb2);
+    return hipGetLastError();
+  }
   size_t lds_floats = (size_t)(Ci + Co + 2 * kMlpChunk) * (kThreads + 1);
   lds_floats += lds_floats & 1;
   const size_t lds = lds_floats * 4 + (size_t)nsum * 8;

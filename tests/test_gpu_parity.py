@@ -376,6 +376,10 @@ def test_adam_steps_match_oracle_for_real_and_complex_parameters():
     (2, 3, 5, 2, 77),                 # ragged tile, hidden below one chunk
     (1, 20, 128, 1, 3000),            # the projection of the benchmark network, several tiles
     (2, 5, 20, 4, 1024),              # whole tiles, four outputs
+    (2, 5, 32, 1, 200),               # one 32-row block of hidden units on the matrix cores, ragged tile
+    (2, 9, 64, 3, 1000),              # two blocks, three outputs, two batch elements
+    (1, 24, 192, 4, 333),             # more than 21 input channels, six blocks
+    (1, 20, 128, 1, 64 * 512 * 17 + 7),  # every block flushes its weight-gradient accumulator once and goes on
 ])
 def test_pointwise_adjoints_match_oracle(shape):
     batch, c_in, hidden, c_out, npts = shape
@@ -400,7 +404,12 @@ def test_pointwise_adjoints_match_oracle(shape):
         want = O.pointwise_linear_bwd(x, w1, gh_in)
         assert rel(host(gx), want["gx"]) <= TOL and rel(host(gW), want["gW"]) <= TOL
         assert rel(host(gb), want["gb"]) <= TOL
-    # the two-layer projection
+    # the two-layer projection: forward, then its adjoint
+    b2 = (0.1 * rng.standard_normal(c_out)).astype(np.float32)
+    u = torch.empty((batch, c_out) + grid, device="cuda")
+    B.fno_pointwise_mlp2(batch, c_in, hidden, c_out, npts, dev(x), dev(w1), dev(b1), dev(w2), dev(b2), u)
+    torch.cuda.synchronize()
+    assert rel(host(u), O.pointwise_mlp2(x, w1, b1, w2, b2)) <= TOL
     gW1 = torch.empty((hidden, c_in), device="cuda")
     gb1 = torch.empty(hidden, device="cuda")
     gW2 = torch.empty((c_out, hidden), device="cuda")
