@@ -97,6 +97,10 @@ __device__ __forceinline__ float2 combine_terms(const float2* w, const float2* x
   return make_float2(acc0.x + acc1.x, acc0.y + acc1.y);
 }
 
+// Row stride of the z-rows in LDS, in complex values: 1 mod 16, so that the rows of the kt bins
+// that adjacent lanes combine start 2 banks apart.
+__host__ __device__ inline int tz_row_stride(int Nz) { return Nz + ((17 - (Nz & 15)) & 15); }
+
 template <int MZ>
 __global__ __launch_bounds__(kThreads) void tz_fwd_kernel(
     const float* __restrict__ x, float2* __restrict__ out, const float2* __restrict__ twt,
@@ -105,7 +109,7 @@ __global__ __launch_bounds__(kThreads) void tz_fwd_kernel(
   HIP_DYNAMIC_SHARED(float, smem)
   const int Pz = Nz / MZ;
   const int sS = Nt + 1;                       // row stride of S in floats
-  const int sT = Nz + 1;                       // row stride of T in float2
+  const int sT = tz_row_stride(Nz);            // row stride of T in float2
   float* S = smem;                             // [ppb][Nz][sS]
   int s_floats = ppb * Nz * sS;
   s_floats += (s_floats & 1);
@@ -249,7 +253,7 @@ __global__ __launch_bounds__(kThreads) void tz_fwd_fast_kernel(
   constexpr int ROT = 16 / QPR > 0 ? 16 / QPR : 1;   // rows that share a rotation
   constexpr int H = NT / 2;
   const int Pz = 1 << pzshift;
-  const int sT = Nz + 1;                       // row stride of T in float2
+  const int sT = tz_row_stride(Nz);            // row stride of T in float2
   float* S = smem;                             // [ppb * Nz] rows of QPR rotated quads
   float2* T = reinterpret_cast<float2*>(smem); // [ppb][mt][sT], same memory, later
   float2* TW = reinterpret_cast<float2*>(smem + region_floats);   // [Lz][Pz]
@@ -527,6 +531,7 @@ __global__ __launch_bounds__(kThreads) void mix_bwd_kernel(
 // Inverse (z, t) with the block epilogue.  One block: all output channels of one (b,nx,ny)
 // column, for the z rows of Q consecutive residue classes (z = Pz*n1 + n2).
 // ------------------------------------------------------------------------------------------
+typedef float v4f __attribute__((ext_vector_type(4)));
 struct EpiArgs {
   const float* u; int Cu; const float* W; int w_so, w_si; const float* bias; float* zsave; int act;
 };
@@ -543,13 +548,61 @@ __global__ __launch_bounds__(kThreads) void zt_inv_kernel(
   const int sY = Nt + 1;
   float2* V = reinterpret_cast<float2*>(smem);                 // [Co][Rz][mt]
   float* Y = smem + 2 * Co * Rz * mt;                          // [Co][Rz][sY]
+  float* WS = Y + ((Co * Rz * sY + 3) & ~3);                   // [Cu][CO]: W of the epilogue, zero past Co
   const int tid = threadIdx.x;
+  if (ep.u != nullptr && ep.Cu <= CO)
+    for (int idx = tid; idx < ep.Cu * CO; idx += kThreads) {
+      const int i = idx / CO, o = idx - i * CO;
+      WS[idx] = o < Co ? ep.W[o * ep.w_so + i * ep.w_si] : 0.f;
+    }
   const long long bxy = blockIdx.x / G;
   const int g = blockIdx.x % G;
   const long long b = bxy / NxNy;
   const long long xy = bxy % NxNy;
   const int kmin = nposz - Lz, kmax = nposz - 1;
 
+  // Z, dense (no power of two in Nz): V[q][(o,kt)] = sum_j conj(tw[j][n2]) a[j][(o,kt)] is a
+  // matrix product; 16x16x4 fp32 MFMA tiles (lane l supplies A[l%16][l/16] and B[l/16][l%16] and
+  // holds rows 4 (l/16) + v of column l%16), real and imaginary part as two accumulators.
+  if constexpr (MZ == 1) {
+    const int wv_id = tid >> 6, lane = tid & 63, lr = lane & 15, lk = lane >> 4;
+    const int ncol = Co * mt;
+    const int nct = (ncol + 15) >> 4, nrt = (Q + 15) >> 4;
+    const int ksteps = (Lz + 3) >> 2;
+    const float2* abase = a + ((b * Co) * NxNy + xy) * (long long)Lz * mt;
+    for (int pair = wv_id; pair < nrt * nct; pair += kThreads / 64) {
+      const int rt = pair / nct, ct = pair - rt * nct;
+      const int q = rt * 16 + lr, n2 = g * Q + q;
+      const bool rowok = q < Q && n2 < Pz;
+      const int n = ct * 16 + lr;
+      const bool colok = n < ncol;
+      const int o = colok ? n / mt : 0, kt = colok ? n - o * mt : 0;
+      const float2* src = abase + (long long)o * NxNy * Lz * mt + kt;
+      v4f re = {0.f, 0.f, 0.f, 0.f}, im = {0.f, 0.f, 0.f, 0.f};
+      for (int s0 = 0; s0 < ksteps; s0 += 8) {       // eight K steps per pass: 16 loads in flight per lane
+        float2 wv[8], av[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+          const int j = 4 * (s0 + u) + lk;
+          const bool ok = j < Lz;
+          wv[u] = (ok && rowok) ? twz[j * Pz + n2] : make_float2(0.f, 0.f);
+          av[u] = (ok && colok) ? src[j * mt] : make_float2(0.f, 0.f);
+        }
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+          re = __builtin_amdgcn_mfma_f32_16x16x4f32(wv[u].x, av[u].x, re, 0, 0, 0);
+          re = __builtin_amdgcn_mfma_f32_16x16x4f32(wv[u].y, av[u].y, re, 0, 0, 0);
+          im = __builtin_amdgcn_mfma_f32_16x16x4f32(wv[u].x, av[u].y, im, 0, 0, 0);
+          im = __builtin_amdgcn_mfma_f32_16x16x4f32(-wv[u].y, av[u].x, im, 0, 0, 0);
+        }
+      }
+#pragma unroll
+      for (int v = 0; v < 4; ++v) {
+        const int qq = rt * 16 + 4 * lk + v;
+        if (qq < Q && colok) V[((o * Rz) + qq) * mt + kt] = make_float2(re[v], im[v]);
+      }
+    }
+  } else
   // Z: gather the kept z-frequencies with their twiddle into MZ bins, inverse FFT over n1
   for (int idx = tid; idx < Co * mt * Q; idx += kThreads) {
     const int q = idx % Q;
@@ -590,7 +643,43 @@ __global__ __launch_bounds__(kThreads) void zt_inv_kernel(
   }
   __syncthreads();
 
-  // T: complex-to-real over t, one thread per (channel, row)
+  // T: complex-to-real over t.  Y[row][t] = sum_kk Vf[row][kk] Wf[kk][t] over the 2 mt real and
+  // imaginary parts of a row: 16x16x4 MFMA tiles, the table operand held in registers.
+  constexpr int kTSteps = 9;
+  if (2 * mt <= 4 * kTSteps) {
+    const int wv_id = tid >> 6, lane = tid & 63, lr = lane & 15, lk = lane >> 4;
+    const float* Vf = reinterpret_cast<const float*>(V);
+    const float* twf = reinterpret_cast<const float*>(twt);
+    const int K2 = 2 * mt, kst = (K2 + 3) >> 2;
+    const int nrows = Co * Rz;
+    const int nrt = (nrows + 15) >> 4, ntt = (Nt + 15) >> 4;
+    for (int tt = 0; tt < ntt; ++tt) {
+      const int t = tt * 16 + lr;
+      float bt[kTSteps];
+#pragma unroll
+      for (int s = 0; s < kTSteps; ++s) {
+        const int kk = 4 * s + lk;
+        bt[s] = (kk < K2 && t < Nt) ? twf[((kk >> 1) * Nt + t) * 2 + (kk & 1)] : 0.f;
+      }
+      for (int rt = wv_id; rt < nrt; rt += kThreads / 64) {
+        const int row = rt * 16 + lr;
+        v4f acc = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int s = 0; s < kTSteps; ++s) {
+          if (s < kst) {
+            const int kk = 4 * s + lk;
+            const float av = (row < nrows && kk < K2) ? Vf[row * K2 + kk] : 0.f;
+            acc = __builtin_amdgcn_mfma_f32_16x16x4f32(av, bt[s], acc, 0, 0, 0);
+          }
+        }
+#pragma unroll
+        for (int v = 0; v < 4; ++v) {
+          const int r2 = rt * 16 + 4 * lk + v;
+          if (r2 < nrows && t < Nt) Y[r2 * sY + t] = acc[v];
+        }
+      }
+    }
+  } else
   for (int idx = tid; idx < Co * Rz; idx += kThreads) {
     const float2* vrow = V + idx * mt;
     float* yrow = Y + idx * sY;
@@ -627,6 +716,18 @@ __global__ __launch_bounds__(kThreads) void zt_inv_kernel(
     if (ep.u != nullptr) {
       const float* up = ep.u + (b * ep.Cu) * Npts + off;
       int i = 0;
+      if (ep.Cu <= CO) {                       // every input channel of the point at once: one round trip
+        float xv[CO];
+#pragma unroll
+        for (int h = 0; h < CO; ++h) xv[h] = h < ep.Cu ? up[h * Npts] : 0.f;
+#pragma unroll
+        for (int h = 0; h < CO; ++h)
+          if (h < ep.Cu) {
+#pragma unroll
+            for (int o = 0; o < CO; ++o) acc[o] = fmaf(WS[h * CO + o], xv[h], acc[o]);
+          }
+        i = ep.Cu;
+      }
       for (; i + 4 <= ep.Cu; i += 4) {         // four input channels per pass: their loads go out together
         float xv[4];
 #pragma unroll
@@ -650,7 +751,7 @@ __global__ __launch_bounds__(kThreads) void zt_inv_kernel(
         const float zv = acc[o] + Y[(o * Rz + r) * sY + t];
         const long long oidx = (b * Co + o) * Npts + off;
         if (ep.zsave != nullptr) ep.zsave[oidx] = zv;
-        out[oidx] = ep.act ? gelu_f(zv) : zv;
+        out[oidx] = ep.act ? gelu_fast_f(zv) : zv;
       }
     }
   }
@@ -670,7 +771,6 @@ __global__ __launch_bounds__(kThreads) void zt_inv_kernel(
 // Blocks that share a (b,nx,ny) column are placed on one XCD so the column's spectrum tile
 // is fetched into that XCD's L2 once.
 // ------------------------------------------------------------------------------------------
-typedef float v4f __attribute__((ext_vector_type(4)));
 
 
 
@@ -2018,12 +2118,14 @@ int pick_q(AxisPlan az, int Nt) {
 size_t tz_fwd_lds(AxisPlan az, int Nt, int mt, int ppb) {
   size_t s_floats = (size_t)ppb * az.N * (Nt + 1);
   s_floats += (s_floats & 1);
-  return s_floats * 4 + (size_t)ppb * mt * (az.N + 1) * 8;
+  return s_floats * 4 + (size_t)ppb * mt * tz_row_stride(az.N) * 8;
 }
 
 size_t zt_inv_lds(AxisPlan az, int Nt, int mt, int Co) {
   const int Rz = pick_q(az, Nt) * az.M;
-  return (size_t)Co * Rz * ((size_t)mt * 8 + (size_t)(Nt + 1) * 4);
+  // V, Y (rounded up to 16 bytes), and the epilogue's weights for up to kMaxCo x kMaxCo channels
+  return (size_t)Co * Rz * (size_t)mt * 8 + (((size_t)Co * Rz * (Nt + 1) + 3) & ~(size_t)3) * 4 +
+         (size_t)kMaxCo * kMaxCo * 4;
 }
 
 int axis_cols(AxisPlan ax, int64_t inner, int rows, int wmax) {
@@ -2055,7 +2157,7 @@ int axis_threads(int items) {
 
 bool tz_fwd_fits(AxisPlan az, int Nt, int mt) { return tz_fwd_lds(az, Nt, mt, 1) <= (size_t)kLdsBudget; }
 bool zt_inv_fits(AxisPlan az, int Nt, int mt, int Co) {
-  return Co <= kMaxCo && zt_inv_lds(az, Nt, mt, Co) <= (size_t)(64 * 1024);
+  return Co <= kMaxCo && zt_inv_lds(az, Nt, mt, Co) <= (size_t)(68 * 1024);
 }
 bool axis_fits(AxisPlan ax) { return (size_t)ax.N * 8 <= (size_t)(32 * 1024); }
 int mfma_q_nw(AxisPlan az, int Nt, int nw);

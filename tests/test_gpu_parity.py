@@ -86,6 +86,9 @@ SMALL = [
     (1, 8, 8, (3, 2, 32, 30), (1, 1, 4, 8), 0),        # matrix-core inverse kernel, t axis padded 30 -> 32
     (2, 3, 3, (2, 3, 32, 12), (1, 1, 6, 4), 0),        # same, 12 -> 16, padded channel tiles
     (1, 20, 20, (2, 2, 64, 30), (1, 1, 12, 8), 0),     # same, width 20, the z and t lengths of the paper's samples
+    (1, 3, 3, (4, 3, 21, 6), (1, 1, 5, 3), 0),         # odd z length: dense z stage of the inverse on 16x16x4 tiles
+    (2, 5, 4, (2, 2, 37, 16), (1, 1, 9, 8), 0),        # same, prime z length, ragged last row group, Cin != Cout
+    (1, 2, 2, (3, 3, 35, 4), (1, 1, 6, 2), 1),         # same, three row tiles per block, symmetric rule
 ]
 
 
