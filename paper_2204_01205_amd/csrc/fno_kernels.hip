@@ -18,6 +18,7 @@ namespace fno {
 namespace {
 
 constexpr int kThreads = 256;
+typedef float v4f __attribute__((ext_vector_type(4)));
 
 __device__ __forceinline__ int kfreq(int j, int L, int npos) { return j < npos ? j : j - L; }
 __device__ __forceinline__ int posmod(int a, int m) { int r = a % m; return r < 0 ? r + m : r; }
@@ -196,6 +197,116 @@ __global__ __launch_bounds__(kThreads) void tz_fwd_kernel(
     const float2* base = T + (p * mt + kt) * sT + Pz * mj;
     const float2* w = twz + jz * Pz;
     out[((plane0 + p) * Lz + jz) * mt + kt] = combine_terms(w, base, 1, Pz);
+  }
+}
+
+// ------------------------------------------------------------------------------------------
+// Forward (t, z) for a z axis with no power of two in its length (the z transform is a dense
+// truncated DFT) and Nt a multiple of 4.  Rows are read straight from memory (one float4 run per
+// thread) for the real-to-complex t stage; the z stage, out[jz][(p,kt)] = sum_n w[jz][n]
+// T[(p,kt)][n], is a matrix product on 16x16x4 fp32 MFMA tiles (lane l supplies A[l%16][l/16] and
+// B[l/16][l%16], holds rows 4 (l/16) + v of column l%16): the 16 columns are the kt bins of
+// 16/mt planes, the z rows (K) are dealt to the four waves, whose partial sums meet in LDS.
+// ------------------------------------------------------------------------------------------
+constexpr int kDenseMT = 3;     // row tiles (16 kept z-frequencies each) per sweep
+// row stride in complex values, 4 mod 16: the 16 lanes of a K step read 4 columns x 4 rows that
+// fall on distinct banks
+__host__ __device__ inline int tzd_row_stride(int Nz) { return Nz + ((20 - (Nz & 15)) & 15); }
+
+__global__ __launch_bounds__(kThreads) void tz_fwd_dense_kernel(
+    const float* __restrict__ x, float2* __restrict__ out, const float2* __restrict__ twt,
+    const float2* __restrict__ twz, long long planes, int Nz, int Nt, int Lz, int mt, int ppb) {
+  HIP_DYNAMIC_SHARED(float, smem)
+  const int sT = tzd_row_stride(Nz);
+  float2* T = reinterpret_cast<float2*>(smem);                 // [16][sT]
+  float2* P = T + 16 * sT;                                     // [4][kDenseMT * 16][16]
+  const int tid = threadIdx.x, w = tid >> 6, lane = tid & 63, lr = lane & 15, lk = lane >> 4;
+  const long long plane0 = (long long)blockIdx.x * ppb;
+  const int np = (int)min((long long)ppb, planes - plane0);
+  const int ncol = np * mt;
+
+  // t stage: one thread per z-row, every kept bin
+  for (int row = tid; row < np * Nz; row += kThreads) {
+    const int p = row / Nz, z = row - p * Nz;
+    const float4* xr = reinterpret_cast<const float4*>(x + ((plane0 + p) * Nz + z) * (long long)Nt);
+    float2 acc[16];
+#pragma unroll
+    for (int kt = 0; kt < 16; ++kt) acc[kt] = make_float2(0.f, 0.f);
+    for (int n = 0; n < Nt; n += 4) {
+      const float4 v = xr[n >> 2];
+#pragma unroll
+      for (int kt = 0; kt < 16; ++kt) {
+        if (kt < mt) {
+          const float2* wp = twt + kt * Nt + n;
+          const float2 w0 = wp[0], w1 = wp[1], w2 = wp[2], w3 = wp[3];
+          acc[kt].x = fmaf(v.x, w0.x, acc[kt].x); acc[kt].y = fmaf(v.x, w0.y, acc[kt].y);
+          acc[kt].x = fmaf(v.y, w1.x, acc[kt].x); acc[kt].y = fmaf(v.y, w1.y, acc[kt].y);
+          acc[kt].x = fmaf(v.z, w2.x, acc[kt].x); acc[kt].y = fmaf(v.z, w2.y, acc[kt].y);
+          acc[kt].x = fmaf(v.w, w3.x, acc[kt].x); acc[kt].y = fmaf(v.w, w3.y, acc[kt].y);
+        }
+      }
+    }
+#pragma unroll
+    for (int kt = 0; kt < 16; ++kt)
+      if (kt < mt) T[(p * mt + kt) * sT + z] = acc[kt];
+  }
+  __syncthreads();
+
+  // z stage
+  const int nmt = (Lz + 15) >> 4, ksteps = (Nz + 3) >> 2;
+  for (int mg = 0; mg < nmt; mg += kDenseMT) {
+    v4f re[kDenseMT], im[kDenseMT];
+#pragma unroll
+    for (int m = 0; m < kDenseMT; ++m) {
+      re[m] = v4f{0.f, 0.f, 0.f, 0.f};
+      im[m] = v4f{0.f, 0.f, 0.f, 0.f};
+    }
+    for (int s0 = w; s0 < ksteps; s0 += 8) {           // two K steps per pass: their loads go out together
+      float2 bv[2], av[2][kDenseMT];
+#pragma unroll
+      for (int u = 0; u < 2; ++u) {
+        const int n = 4 * (s0 + 4 * u) + lk;
+        const bool nok = n < Nz;
+        bv[u] = (nok && lr < ncol) ? T[lr * sT + n] : make_float2(0.f, 0.f);
+#pragma unroll
+        for (int m = 0; m < kDenseMT; ++m) {
+          const int jz = (mg + m) * 16 + lr;
+          av[u][m] = (nok && jz < Lz) ? twz[jz * Nz + n] : make_float2(0.f, 0.f);
+        }
+      }
+#pragma unroll
+      for (int u = 0; u < 2; ++u)
+#pragma unroll
+        for (int m = 0; m < kDenseMT; ++m) {
+          re[m] = __builtin_amdgcn_mfma_f32_16x16x4f32(av[u][m].x, bv[u].x, re[m], 0, 0, 0);
+          re[m] = __builtin_amdgcn_mfma_f32_16x16x4f32(-av[u][m].y, bv[u].y, re[m], 0, 0, 0);
+          im[m] = __builtin_amdgcn_mfma_f32_16x16x4f32(av[u][m].x, bv[u].y, im[m], 0, 0, 0);
+          im[m] = __builtin_amdgcn_mfma_f32_16x16x4f32(av[u][m].y, bv[u].x, im[m], 0, 0, 0);
+        }
+    }
+#pragma unroll
+    for (int m = 0; m < kDenseMT; ++m)
+#pragma unroll
+      for (int v = 0; v < 4; ++v)
+        P[(w * (kDenseMT * 16) + m * 16 + 4 * lk + v) * 16 + lr] = make_float2(re[m][v], im[m][v]);
+    __syncthreads();
+    for (int idx = tid; idx < np * (kDenseMT * 16) * mt; idx += kThreads) {
+      const int kt = idx % mt;
+      const int jzl = (idx / mt) % (kDenseMT * 16);
+      const int p = idx / (mt * kDenseMT * 16);
+      const int jz = mg * 16 + jzl;
+      if (jz < Lz) {
+        const int col = p * mt + kt;
+        float2 sum = make_float2(0.f, 0.f);
+#pragma unroll
+        for (int ww = 0; ww < kThreads / 64; ++ww) {
+          const float2 v = P[(ww * (kDenseMT * 16) + jzl) * 16 + col];
+          sum.x += v.x; sum.y += v.y;
+        }
+        out[((plane0 + p) * Lz + jz) * mt + kt] = sum;
+      }
+    }
+    __syncthreads();
   }
 }
 
@@ -531,7 +642,6 @@ __global__ __launch_bounds__(kThreads) void mix_bwd_kernel(
 // Inverse (z, t) with the block epilogue.  One block: all output channels of one (b,nx,ny)
 // column, for the z rows of Q consecutive residue classes (z = Pz*n1 + n2).
 // ------------------------------------------------------------------------------------------
-typedef float v4f __attribute__((ext_vector_type(4)));
 struct EpiArgs {
   const float* u; int Cu; const float* W; int w_so, w_si; const float* bias; float* zsave; int act;
 };
@@ -2232,6 +2342,17 @@ hipError_t launch_tz_fwd(const float* x, float2* out, const float2* twt, const f
 #undef FNO_TZF_M
 #undef FNO_TZF
     return hipGetLastError();
+  }
+  if (az.M == 1 && Nt % 4 == 0 && mt <= 16 && (reinterpret_cast<uintptr_t>(x) & 15) == 0) {
+    const int ppb = 16 / mt;
+    const size_t lds = (size_t)16 * tzd_row_stride(az.N) * 8 + (size_t)(kThreads / 64) * kDenseMT * 16 * 16 * 8;
+    const int64_t nblk = (planes + ppb - 1) / ppb;
+    if (nblk > 0x7fffffffLL) return hipErrorInvalidValue;
+    if (lds <= (size_t)(150 * 1024)) {
+      hipLaunchKernelGGL(tz_fwd_dense_kernel, dim3((unsigned)nblk), dim3(kThreads), lds, s, x, out, twt, twz,
+                         (long long)planes, az.N, Nt, az.L, mt, ppb);
+      return hipGetLastError();
+    }
   }
   int ppb = 1;
   // enough rows to occupy the block, within an LDS share that keeps several blocks per CU

@@ -89,6 +89,7 @@ SMALL = [
     (1, 3, 3, (4, 3, 21, 6), (1, 1, 5, 3), 0),         # odd z length: dense z stage of the inverse on 16x16x4 tiles
     (2, 5, 4, (2, 2, 37, 16), (1, 1, 9, 8), 0),        # same, prime z length, ragged last row group, Cin != Cout
     (1, 2, 2, (3, 3, 35, 4), (1, 1, 6, 2), 1),         # same, three row tiles per block, symmetric rule
+    (1, 2, 2, (2, 2, 135, 8), (1, 1, 30, 3), 0),       # dense forward z stage: two sweeps of row tiles, 15 of 16 columns
 ]
 
 
