@@ -646,7 +646,49 @@ struct EpiArgs {
   const float* u; int Cu; const float* W; int w_so, w_si; const float* bias; float* zsave; int act;
 };
 
-template <int MZ, int CO>
+// The epilogue of one grid point: all output channels.  EXACT: the channel counts fill the
+// register tile, so no per-channel guards (they cost scalar registers the compiler then spills).
+template <int CO, bool EXACT>
+__device__ __forceinline__ void zt_epilogue_point(const EpiArgs& ep, int Co, const float* WS, const float* Y,
+                                                  int Rz, int sY, int r, int t, long long b, long long off,
+                                                  long long Npts, float* __restrict__ out) {
+  float acc[CO];
+#pragma unroll
+  for (int o = 0; o < CO; ++o) acc[o] = (ep.bias != nullptr && (EXACT || o < Co)) ? ep.bias[o] : 0.f;
+  if (ep.u != nullptr) {
+    const float* up = ep.u + (b * ep.Cu) * Npts + off;
+    int i = 0;
+    if (EXACT || ep.Cu <= CO) {              // every input channel of the point at once: one round trip
+      float xv[CO];
+#pragma unroll
+      for (int h = 0; h < CO; ++h) xv[h] = (EXACT || h < ep.Cu) ? up[h * Npts] : 0.f;
+#pragma unroll
+      for (int h = 0; h < CO; ++h)
+        if (EXACT || h < ep.Cu) {
+#pragma unroll
+          for (int o = 0; o < CO; ++o) acc[o] = fmaf(WS[h * CO + o], xv[h], acc[o]);
+        }
+      i = ep.Cu;
+    }
+    for (; i < ep.Cu; ++i) {                 // more input channels than the register tile: one at a time
+      const float xv = up[i * Npts];
+#pragma unroll
+      for (int o = 0; o < CO; ++o)
+        if (o < Co) acc[o] = fmaf(ep.W[o * ep.w_so + i * ep.w_si], xv, acc[o]);
+    }
+  }
+#pragma unroll
+  for (int o = 0; o < CO; ++o) {
+    if (EXACT || o < Co) {
+      const float zv = acc[o] + Y[(o * Rz + r) * sY + t];
+      const long long oidx = (b * Co + o) * Npts + off;
+      if (ep.zsave != nullptr) ep.zsave[oidx] = zv;
+      out[oidx] = ep.act ? gelu_fast_f(zv) : zv;
+    }
+  }
+}
+
+template <int MZ, int CO, bool EXACT>
 __global__ __launch_bounds__(kThreads) void zt_inv_kernel(
     const float2* __restrict__ a, float* __restrict__ out, const float2* __restrict__ twt,
     const float2* __restrict__ twz, int Co, int NxNy, int Nz, int Nt, int Lz, int nposz, int mt,
@@ -820,50 +862,7 @@ __global__ __launch_bounds__(kThreads) void zt_inv_kernel(
     if (g * Q + (r % Q) >= Pz) continue;
     const int z = Pz * (r / Q) + g * Q + (r % Q);
     const long long off = (xy * Nz + z) * Nt + t;
-    float acc[CO];
-#pragma unroll
-    for (int o = 0; o < CO; ++o) acc[o] = (ep.bias != nullptr && o < Co) ? ep.bias[o] : 0.f;
-    if (ep.u != nullptr) {
-      const float* up = ep.u + (b * ep.Cu) * Npts + off;
-      int i = 0;
-      if (ep.Cu <= CO) {                       // every input channel of the point at once: one round trip
-        float xv[CO];
-#pragma unroll
-        for (int h = 0; h < CO; ++h) xv[h] = h < ep.Cu ? up[h * Npts] : 0.f;
-#pragma unroll
-        for (int h = 0; h < CO; ++h)
-          if (h < ep.Cu) {
-#pragma unroll
-            for (int o = 0; o < CO; ++o) acc[o] = fmaf(WS[h * CO + o], xv[h], acc[o]);
-          }
-        i = ep.Cu;
-      }
-      for (; i + 4 <= ep.Cu; i += 4) {         // four input channels per pass: their loads go out together
-        float xv[4];
-#pragma unroll
-        for (int h = 0; h < 4; ++h) xv[h] = up[(i + h) * Npts];
-#pragma unroll
-        for (int h = 0; h < 4; ++h)
-#pragma unroll
-          for (int o = 0; o < CO; ++o)
-            if (o < Co) acc[o] = fmaf(ep.W[o * ep.w_so + (i + h) * ep.w_si], xv[h], acc[o]);
-      }
-      for (; i < ep.Cu; ++i) {
-        const float xv = up[i * Npts];
-#pragma unroll
-        for (int o = 0; o < CO; ++o)
-          if (o < Co) acc[o] = fmaf(ep.W[o * ep.w_so + i * ep.w_si], xv, acc[o]);
-      }
-    }
-#pragma unroll
-    for (int o = 0; o < CO; ++o) {
-      if (o < Co) {
-        const float zv = acc[o] + Y[(o * Rz + r) * sY + t];
-        const long long oidx = (b * Co + o) * Npts + off;
-        if (ep.zsave != nullptr) ep.zsave[oidx] = zv;
-        out[oidx] = ep.act ? gelu_fast_f(zv) : zv;
-      }
-    }
+    zt_epilogue_point<CO, EXACT>(ep, Co, WS, Y, Rz, sY, r, t, b, off, Npts, out);
   }
 }
 
@@ -2582,10 +2581,19 @@ hipError_t launch_zt_inv(const float2* a, float* out, const float2* twt, const f
   const int64_t nblk = ncols * G;
   if (nblk > 0x7fffffffLL) return hipErrorInvalidValue;
   const size_t lds = zt_inv_lds(az, Nt, mt, Co);
-#define FNO_ZT_CALL(COV)                                                                          \
-  FNO_DISPATCH_M(az.M, hipLaunchKernelGGL((zt_inv_kernel<MM, COV>), dim3((unsigned)nblk),         \
-                                          dim3(kThreads), lds, s, a, out, twt, twz, Co, NxNy,     \
-                                          az.N, Nt, az.L, az.npos, mt, Q, e))
+  // the channel counts fill the kernel's register tile exactly: the variant without per-channel guards
+#define FNO_ZT_CALL(COV)                                                                              \
+  do {                                                                                                \
+    if (Co == COV && (e.u == nullptr || e.Cu == COV)) {                                               \
+      FNO_DISPATCH_M(az.M, hipLaunchKernelGGL((zt_inv_kernel<MM, COV, true>), dim3((unsigned)nblk),   \
+                                              dim3(kThreads), lds, s, a, out, twt, twz, Co, NxNy,     \
+                                              az.N, Nt, az.L, az.npos, mt, Q, e));                    \
+    } else {                                                                                          \
+      FNO_DISPATCH_M(az.M, hipLaunchKernelGGL((zt_inv_kernel<MM, COV, false>), dim3((unsigned)nblk),  \
+                                              dim3(kThreads), lds, s, a, out, twt, twz, Co, NxNy,     \
+                                              az.N, Nt, az.L, az.npos, mt, Q, e));                    \
+    }                                                                                                 \
+  } while (0)
   if (Co <= 8) { FNO_ZT_CALL(8); }
   else if (Co <= 20) { FNO_ZT_CALL(20); }
   else { FNO_ZT_CALL(32); }
