@@ -426,6 +426,24 @@ def time_lift(a, wt, bt, wc, bc):
     return channel_affine(a1, wc, bc)
 
 
+def time_lift_bwd(a, wt, bt, wc, g):
+    """Adjoint of time_lift for a cotangent g of its output, the two lifts of eqs. (8)-(9) taken
+    backwards one after the other: first through nu = W_c a_1 + b_c (channel axis), then through
+    a_1 = W_t a + b_t (time axis).  Sums over broadcast axes are the adjoint of the broadcast
+    (Sec. 2.1).  Returns ga (shape of a), gWt (nt,), gbt (nt,), gWc (C, Cin), gbc (C,)."""
+    a = np.asarray(a, np.float64)
+    wt = np.asarray(wt, np.float64).reshape(-1)
+    bt = np.asarray(bt, np.float64).reshape(-1)
+    a1 = np.tensordot(a, wt.reshape(-1, 1), axes=([5], [1])) + bt
+    chan = pointwise_linear_bwd(a1, wc, g)                 # through W_c: g_{a_1}, gWc, gbc
+    ga1 = chan["gx"]                                       # (B, Cin, Nx, Ny, Nz, nt)
+    lead = tuple(range(ga1.ndim - 1))
+    gwt = np.sum(ga1 * a, axis=lead)                       # a broadcasts along the time axis
+    gbt = np.sum(ga1, axis=lead)
+    ga = np.tensordot(ga1, wt, axes=([5], [0]))[..., None]
+    return {"ga": ga, "gWt": gwt, "gbt": gbt, "gWc": chan["gW"], "gbc": chan["gb"]}
+
+
 def rel_l2_loss(pred, target):
     """Relative L2 misfit of Sec. 4: ||pred - target||_2 / ||target||_2 over all entries."""
     pred = np.asarray(pred, np.float64)

@@ -486,6 +486,54 @@ def test_time_lift_against_loops_closed_forms_and_the_channel_lift():
     assert np.max(np.abs(d - lin)) <= 1e-12
 
 
+def test_time_lift_adjoint_against_loops_and_finite_differences():
+    """The adjoint of the two lifts of eqs. (8)-(9): every gradient against plain loops over all
+    indices and against central differences of L = <g, time_lift(...)>."""
+    rng = np.random.default_rng(37)
+    B, Cin, C, grid, nt = 2, 3, 4, (2, 2, 3), 5
+    a = rng.standard_normal((B, Cin) + grid + (1,))
+    wt, bt = rng.standard_normal(nt), rng.standard_normal(nt)
+    wc, bc = rng.standard_normal((C, Cin)), rng.standard_normal(C)
+    g = rng.standard_normal((B, C) + grid + (nt,))
+    got = O.time_lift_bwd(a, wt, bt, wc, g)
+    # loops: d nu[b,c,p,t] / d each parameter, from nu = sum_j wc[c,j] (wt[t] a[b,j,p] + bt[t]) + bc[c]
+    gwt, gbt, gwc, gbc, ga = np.zeros(nt), np.zeros(nt), np.zeros((C, Cin)), np.zeros(C), np.zeros(a.shape)
+    for b in range(B):
+        for c in range(C):
+            for x in range(grid[0]):
+                for y in range(grid[1]):
+                    for z in range(grid[2]):
+                        for t in range(nt):
+                            gv = g[b, c, x, y, z, t]
+                            gbc[c] += gv
+                            for j in range(Cin):
+                                av = a[b, j, x, y, z, 0]
+                                gwc[c, j] += gv * (wt[t] * av + bt[t])
+                                gwt[t] += gv * wc[c, j] * av
+                                gbt[t] += gv * wc[c, j]
+                                ga[b, j, x, y, z, 0] += gv * wc[c, j] * wt[t]
+    for name, want in (("gWt", gwt), ("gbt", gbt), ("gWc", gwc), ("gbc", gbc), ("ga", ga)):
+        assert np.max(np.abs(got[name] - want)) <= 1e-12 * max(1.0, np.max(np.abs(want))), name
+    # central differences (the map is affine in each argument: exact up to rounding)
+    def L(a_, wt_, bt_, wc_, bc_):
+        return float(np.sum(g * O.time_lift(a_, wt_, bt_, wc_, bc_)))
+    h = 1e-3
+    for name, idx, arg in (("gWt", (2,), 1), ("gbt", (4,), 2), ("gWc", (1, 2), 3), ("gbc", (3,), 4),
+                           ("ga", (1, 2, 1, 0, 2, 0), 0)):
+        args = [a, wt, bt, wc, bc]
+        plus = [v.copy() for v in args]
+        minus = [v.copy() for v in args]
+        plus[arg][idx] += h
+        minus[arg][idx] -= h
+        fd = (L(*plus) - L(*minus)) / (2 * h)
+        assert abs(fd - got[name][idx]) <= 1e-8 * max(1.0, abs(fd)), name
+    # W_t = 1, b_t = 0 reduces the channel part to the adjoint of the channel lift summed over time
+    ones = O.time_lift_bwd(a, np.ones(nt), np.zeros(nt), wc, g)
+    lin = O.pointwise_linear_bwd(a, wc, g.sum(axis=5, keepdims=True))
+    assert np.max(np.abs(ones["gWc"] - lin["gW"])) <= 1e-12
+    assert np.max(np.abs(ones["ga"] - lin["gx"])) <= 1e-12
+
+
 def test_relative_l2_loss_and_its_gradient():
     """Sec. 4: L(y, yhat) = ||y - yhat||_2 / ||yhat||_2."""
     # a 3-4-5 example by hand: difference (3, 4, 0), target (0, 0, 10) -> 5 / 10
