@@ -26,7 +26,7 @@ def parse():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=10)
     ap.add_argument("--warmup", type=int, default=3)
-    ap.add_argument("--config", default="cfg4", help="workload name from synth.CONFIGS (block forward; cfg5: forward + backward), or time_lift")
+    ap.add_argument("--config", default="cfg4", help="workload name from synth.CONFIGS (block forward; cfg5: forward + backward), or time_lift, time_lift_bwd")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--network", action="store_true",
                     help="time one training step of the whole network of the workload (cfg3: lift, blocks, "
@@ -66,8 +66,9 @@ def cpu_baseline(cfg):
             "host_cores_visible": len(os.sched_getaffinity(0))}
 
 
-def time_lift_bench(args, torch, B):
-    """The fused input lifts (fno_time_lift) at the largest grid: 2 -> 20 channels, 1 -> 32 time steps."""
+def time_lift_bench(args, torch, B, adjoint=False):
+    """The fused input lifts (fno_time_lift), or their adjoint with respect to the parameters
+    (fno_time_lift_bwd), at the largest grid: 2 -> 20 channels, 1 -> 32 time steps."""
     grid, nt, c_in, c_out = (256, 256, 128), 32, 2, 20
     ns = grid[0] * grid[1] * grid[2]
     torch.cuda.set_device(0)
@@ -80,8 +81,18 @@ def time_lift_bench(args, torch, B):
     bc = torch.randn(c_out, device="cuda", generator=gen)
     out = torch.empty((1, c_out, ns, nt), device="cuda")
 
+    if adjoint:
+        out.normal_(generator=gen)               # plays the cotangent of the lifted tensor
+        ws = torch.empty(B.fno_time_lift_bwd_workspace_bytes(c_in, c_out, nt) // 4 + 2, dtype=torch.float32,
+                         device="cuda")
+        gwt, gbt = torch.empty_like(wt), torch.empty_like(bt)
+        gwc, gbc = torch.empty_like(wc), torch.empty_like(bc)
+
     def step():
-        B.fno_time_lift(1, c_in, c_out, ns, nt, a, wt, bt, wc, bc, out)
+        if adjoint:
+            B.fno_time_lift_bwd(1, c_in, c_out, ns, nt, a, wt, bt, wc, out, gwt, gbt, gwc, gbc, ws)
+        else:
+            B.fno_time_lift(1, c_in, c_out, ns, nt, a, wt, bt, wc, bc, out)
 
     for _ in range(args.warmup):
         step()
@@ -97,16 +108,17 @@ def time_lift_bench(args, torch, B):
     ms = 1e3 * dt / args.steps
     launch_ms = e0.elapsed_time(e1) / args.steps
     pc = float(c_out) * ns * nt
-    nbytes = 4.0 * pc + 4.0 * c_in * ns          # output written once, input read once
+    nbytes = 4.0 * pc + 4.0 * c_in * ns          # lifted tensor written (adjoint: its cotangent read) once, input read once
+    name = "time_lift_bwd" if adjoint else "time_lift"
     print(json.dumps({
         "metric": "FNO spectral layer Gpoint-channels/s + achieved HBM GB/s on 1 MI355X",
         "value": pc / (ms * 1e-3) / 1e9, "unit": "Gpoint-channels/s", "n_gpus": 1, "steps": args.steps,
         "warmup": args.warmup, "ms_per_step": ms, "higher_is_better": True, "scaling": "weak",
         "vs_baseline": None, "dtype": "f32", "data": "synthetic",
-        "config": {"workload": f"time_lift: fno_time_lift, batch 1, {c_in} -> {c_out} channels, grid "
+        "config": {"workload": f"{name}: fno_{name}, batch 1, {c_in} -> {c_out} channels, grid "
                                f"{grid[0]}x{grid[1]}x{grid[2]}, 1 -> {nt} time steps",
                    "global_batch": 1, "parallelism": "single GPU"},
-        "roofline": {"kernel": "time_lift", "bound": "hbm", "achieved": nbytes / (launch_ms * 1e-3) / 1e9,
+        "roofline": {"kernel": name, "bound": "hbm", "achieved": nbytes / (launch_ms * 1e-3) / 1e9,
                      "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": nbytes / (launch_ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
                      "traffic": None, "avg_launch_ms": launch_ms, "algorithmic_bytes_per_launch": nbytes},
     }))
@@ -211,8 +223,8 @@ def main():
         torch.cuda.synchronize()
         print(json.dumps({"calibrate_copy_bytes_each_way": 4 * (1 << 30), "copies": 3}))
         return
-    if args.config == "time_lift":
-        time_lift_bench(args, torch, B)
+    if args.config in ("time_lift", "time_lift_bwd"):
+        time_lift_bench(args, torch, B, adjoint=args.config == "time_lift_bwd")
         return
     if args.network:
         network_step_bench(args, torch, B, synth)

@@ -137,6 +137,20 @@ int fno_time_lift(int32_t batch, int32_t c_in, int32_t c_out, int64_t nspace, in
                   const float* Wt, const float* bt, const float* Wc, const float* bc, float* out,
                   void* stream);
 
+/* Adjoint of fno_time_lift (Sec. 2.4, eqs. (8)-(9); sums over broadcast axes, Sec. 2.1) with
+ * respect to its parameters, for a cotangent g [B][c_out][nspace][nt] of its output:
+ *   gbc[o] = sum g,  gWc[o][i] = sum g (Wt[t] a[b][i][s] + bt[t]),
+ *   gWt[t] = sum g Wc[o][i] a[b][i][s],  gbt[t] = sum g Wc[o][i]
+ * (each over every index not on the left).  The input a is data: its gradient is not formed.
+ * Every output is nullable and overwritten; fixed summation order, the same bits on every run.
+ * ws: device scratch of fno_time_lift_bwd_workspace_bytes(c_in, c_out, nt) bytes, 8-byte aligned,
+ * owned by the caller.  c_in <= 8, batch <= 1024.  Asynchronous on `stream`; nothing is
+ * launched on an argument error. */
+int fno_time_lift_bwd_workspace_bytes(int32_t c_in, int32_t c_out, int32_t nt, size_t* bytes);
+int fno_time_lift_bwd(int32_t batch, int32_t c_in, int32_t c_out, int64_t nspace, int32_t nt, const float* a,
+                      const float* Wt, const float* bt, const float* Wc, const float* g, float* gWt,
+                      float* gbt, float* gWc, float* gbc, void* ws, size_t ws_bytes, void* stream);
+
 /* Adjoints of fno_pointwise_linear and fno_pointwise_mlp2 (what the backward of a whole network
  * needs around its blocks).  For a cotangent g of the output:
  *   linear:  gx = W^T g  [B][c_in][npoints];  gW[o][i] = sum g[b][o][p] x[b][i][p];  gb[o] = sum g

@@ -26,6 +26,7 @@ EXPORTS = [
     "fno_block_fwd", "fno_block_bwd", "fno_pointwise_linear", "fno_pointwise_mlp2", "fno_time_lift",
     "fno_rel_l2_workspace_bytes", "fno_rel_l2_loss", "fno_adam_step",
     "fno_pointwise_bwd_workspace_bytes", "fno_pointwise_linear_bwd", "fno_pointwise_mlp2_bwd",
+    "fno_time_lift_bwd_workspace_bytes", "fno_time_lift_bwd",
     "fno_status_string", "fno_timing_enable", "fno_timing_read",
 ]
 
@@ -165,6 +166,22 @@ def fno_time_lift(batch, c_in, c_out, nspace, nt, a, Wt, bt, Wc, bc, out) -> Non
                                ctypes.c_int64(nspace), ctypes.c_int32(nt), _ptr(a, name="a"),
                                _ptr(Wt, name="Wt"), _ptr(bt, name="bt"), _ptr(Wc, name="Wc"),
                                _ptr(bc, name="bc"), _ptr(out, name="out"), _stream()))
+
+
+def fno_time_lift_bwd_workspace_bytes(c_in, c_out, nt) -> int:
+    n = ctypes.c_size_t(0)
+    _check(lib().fno_time_lift_bwd_workspace_bytes(ctypes.c_int32(c_in), ctypes.c_int32(c_out), ctypes.c_int32(nt),
+                                                   ctypes.byref(n)))
+    return int(n.value)
+
+
+def fno_time_lift_bwd(batch, c_in, c_out, nspace, nt, a, Wt, bt, Wc, g, gWt, gbt, gWc, gbc, ws) -> None:
+    _check(lib().fno_time_lift_bwd(ctypes.c_int32(batch), ctypes.c_int32(c_in), ctypes.c_int32(c_out),
+                                   ctypes.c_int64(nspace), ctypes.c_int32(nt), _ptr(a, name="a"),
+                                   _ptr(Wt, name="Wt"), _ptr(bt, name="bt"), _ptr(Wc, name="Wc"),
+                                   _ptr(g, name="g"), _ptr(gWt, name="gWt"), _ptr(gbt, name="gbt"),
+                                   _ptr(gWc, name="gWc"), _ptr(gbc, name="gbc"), _ptr(ws, name="ws"),
+                                   ctypes.c_size_t(ws.numel() * ws.element_size()), _stream()))
 
 
 def fno_pointwise_bwd_workspace_bytes(c_in, hidden, c_out) -> int:

@@ -386,6 +386,25 @@ int fno_time_lift(int32_t batch, int32_t c_in, int32_t c_out, int64_t nspace, in
   return FNO_OK;
 }
 
+int fno_time_lift_bwd_workspace_bytes(int32_t c_in, int32_t c_out, int32_t nt, size_t* bytes) {
+  if (bytes == nullptr || c_in < 1 || c_out < 1 || nt < 1) { set_detail("positive sizes and bytes are required"); return FNO_EINVAL; }
+  *bytes = fno::time_lift_bwd_workspace_bytes(c_in, c_out, nt);
+  return FNO_OK;
+}
+
+int fno_time_lift_bwd(int32_t batch, int32_t c_in, int32_t c_out, int64_t nspace, int32_t nt, const float* a,
+                      const float* Wt, const float* bt, const float* Wc, const float* g, float* gWt,
+                      float* gbt, float* gWc, float* gbc, void* ws, size_t ws_bytes, void* stream) {
+  if (batch < 1 || c_in < 1 || c_out < 1 || nspace < 1 || nt < 1) { set_detail("sizes must be positive"); return FNO_EINVAL; }
+  if (a == nullptr || Wt == nullptr || Wc == nullptr || g == nullptr || ws == nullptr) { set_detail("a, Wt, Wc, g and ws are required"); return FNO_EINVAL; }
+  if (c_in > 8 || batch > 1024 || (int64_t)c_out * nt > (int64_t)1 << 20) { set_detail("time_lift_bwd covers c_in <= 8, batch <= 1024, c_out * nt <= 2^20"); return FNO_EUNSUPPORTED; }
+  if (ws_bytes < fno::time_lift_bwd_workspace_bytes(c_in, c_out, nt)) { set_detail("workspace too small"); return FNO_ENOSPC; }
+  if (reinterpret_cast<uintptr_t>(ws) % 8 != 0) { set_detail("ws must be 8-byte aligned"); return FNO_EINVAL; }
+  FNO_HIP(fno::launch_time_lift_bwd(batch, c_in, c_out, nspace, nt, a, Wt, bt, Wc, g, gWt, gbt, gWc, gbc, ws,
+                                    static_cast<hipStream_t>(stream)));
+  return FNO_OK;
+}
+
 int fno_pointwise_bwd_workspace_bytes(int32_t c_in, int32_t hidden, int32_t c_out, size_t* bytes) {
   if (bytes == nullptr || c_in < 1 || hidden < 0 || c_out < 1) { set_detail("positive widths and bytes are required"); return FNO_EINVAL; }
   *bytes = fno::pointwise_bwd_workspace_bytes(c_in, hidden, c_out);

@@ -75,6 +75,13 @@ hipError_t launch_pointwise_mlp2(int B, int Ci, int H, int Co, int64_t np, const
 hipError_t launch_time_lift(int B, int Ci, int Co, int64_t np, int Nt, const float* a, const float* wt,
                             const float* bt, const float* wc, const float* bc, float* out, hipStream_t s);
 
+// Adjoint of the fused lifts with respect to Wt, bt, Wc, bc (each output nullable).  ws: device
+// scratch of time_lift_bwd_workspace_bytes(Ci, Co, Nt) bytes.  Ci <= 8, B <= 1024.
+size_t time_lift_bwd_workspace_bytes(int Ci, int Co, int Nt);
+hipError_t launch_time_lift_bwd(int B, int Ci, int Co, int64_t S, int Nt, const float* a, const float* wt,
+                                const float* bt, const float* wc, const float* g, float* gwt, float* gbt,
+                                float* gwc, float* gbc, void* ws, hipStream_t s);
+
 // Relative L2 misfit ||pred - target|| / ||target|| (device scalar `loss`, nullable) and its
 // gradient with respect to pred (nullable); ws: rel_l2_workspace_bytes() of scratch.
 size_t rel_l2_workspace_bytes();

@@ -2181,6 +2181,109 @@ __global__ __launch_bounds__(kThreads) void time_lift_kernel(
   }
 }
 
+// Adjoint of the fused lifts (eqs. (8)-(9)) with respect to their parameters.  With
+//   G0[o][t] = sum_{b,s} g[b][o][s][t]   and   G1[i][o][t] = sum_{b,s} g[b][o][s][t] a[b][i][s]
+// every gradient is a small contraction:  gbc[o] = sum_t G0,  gWc[o][i] = sum_t (Wt[t] G1 + bt[t] G0),
+// gWt[t] = sum_{o,i} Wc[o][i] G1,  gbt[t] = sum_{o,i} Wc[o][i] G0.  The sweep over g (the only large
+// tensor) keeps one (o, t) pair per thread, so a wave reads whole 128-byte runs of t and the input
+// value a[b][i][s] is the same for all its lanes; a chunk of space positions per block row, fp32
+// sums of 64 terms added into doubles, one partial per (chunk, pair) in a fixed order.
+constexpr int kLiftChunks = 1024;      // partial-sum slots of the sweep
+template <int CI>
+__global__ __launch_bounds__(kThreads) void time_lift_bwd_kernel(
+    int Ci, int Co, long long S, int Nt, int cpb, const float* __restrict__ a, const float* __restrict__ g,
+    double* __restrict__ part) {
+  const int pair = blockIdx.x * kThreads + threadIdx.x;
+  const int npair = Co * Nt;
+  const long long b = blockIdx.y / cpb;
+  const int c = blockIdx.y - (int)b * cpb;
+  const long long len = (S + cpb - 1) / cpb;
+  const long long s0 = c * len, s1 = min(S, s0 + len);
+  const bool live = pair < npair;
+  const int o = live ? pair / Nt : 0, t = live ? pair - o * Nt : 0;
+  const float* gp = g + ((b * Co + o) * S) * Nt + t;
+  const float* ap = a + (b * Ci) * S;
+  double d0 = 0.0, d1[CI];
+#pragma unroll
+  for (int i = 0; i < CI; ++i) d1[i] = 0.0;
+  for (long long sb = s0; sb < s1; sb += 64) {
+    float f0 = 0.f, f1[CI];
+#pragma unroll
+    for (int i = 0; i < CI; ++i) f1[i] = 0.f;
+    const long long se = min(s1, sb + 64);
+    long long sp = sb;
+    for (; sp + 8 <= se; sp += 8) {              // eight positions per pass: their loads go out together
+      float gv[8];
+#pragma unroll
+      for (int u = 0; u < 8; ++u) gv[u] = live ? gp[(sp + u) * Nt] : 0.f;
+#pragma unroll
+      for (int u = 0; u < 8; ++u) {
+        f0 += gv[u];
+#pragma unroll
+        for (int i = 0; i < CI; ++i)
+          if (i < Ci) f1[i] = fmaf(gv[u], ap[i * S + sp + u], f1[i]);
+      }
+    }
+    for (; sp < se; ++sp) {
+      const float gv = live ? gp[sp * Nt] : 0.f;
+      f0 += gv;
+#pragma unroll
+      for (int i = 0; i < CI; ++i)
+        if (i < Ci) f1[i] = fmaf(gv, ap[i * S + sp], f1[i]);
+    }
+    d0 += (double)f0;
+#pragma unroll
+    for (int i = 0; i < CI; ++i) d1[i] += (double)f1[i];
+  }
+  if (live) {
+    double* dst = part + ((long long)blockIdx.y * (Ci + 1)) * npair + pair;
+    dst[0] = d0;
+#pragma unroll
+    for (int i = 0; i < CI; ++i)
+      if (i < Ci) dst[(long long)(i + 1) * npair] = d1[i];
+  }
+}
+
+// G[k][pair] = sum over the chunks, in order
+__global__ __launch_bounds__(kThreads) void time_lift_bwd_reduce_kernel(const double* __restrict__ part, int nchunk,
+                                                                        int nent, double* __restrict__ G) {
+  const int e = blockIdx.x * kThreads + threadIdx.x;
+  if (e >= nent) return;
+  double sum = 0.0;
+  for (int c = 0; c < nchunk; ++c) sum += part[(long long)c * nent + e];
+  G[e] = sum;
+}
+
+// the four small contractions, one output per thread
+__global__ __launch_bounds__(kThreads) void time_lift_bwd_final_kernel(
+    int Ci, int Co, int Nt, const double* __restrict__ G, const float* __restrict__ wt,
+    const float* __restrict__ bt, const float* __restrict__ wc, float* __restrict__ gwt,
+    float* __restrict__ gbt, float* __restrict__ gwc, float* __restrict__ gbc) {
+  const int npair = Co * Nt;
+  const int nout = 2 * Nt + Co * Ci + Co;
+  for (int q = threadIdx.x; q < nout; q += kThreads) {
+    double sum = 0.0;
+    if (q < 2 * Nt) {                            // gWt[t] (q < Nt) or gbt[t]
+      const int t = q < Nt ? q : q - Nt;
+      for (int o = 0; o < Co; ++o)
+        for (int i = 0; i < Ci; ++i)
+          sum += (double)wc[o * Ci + i] * (q < Nt ? G[(long long)(i + 1) * npair + o * Nt + t] : G[o * Nt + t]);
+      float* dst = q < Nt ? gwt : gbt;
+      if (dst != nullptr) dst[t] = (float)sum;
+    } else if (q < 2 * Nt + Co * Ci) {           // gWc[o][i]
+      const int oi = q - 2 * Nt, o = oi / Ci, i = oi - o * Ci;
+      for (int t = 0; t < Nt; ++t)
+        sum += (double)wt[t] * G[(long long)(i + 1) * npair + o * Nt + t] +
+               (bt != nullptr ? (double)bt[t] * G[o * Nt + t] : 0.0);
+      if (gwc != nullptr) gwc[oi] = (float)sum;
+    } else {                                     // gbc[o]
+      const int o = q - 2 * Nt - Co * Ci;
+      for (int t = 0; t < Nt; ++t) sum += G[o * Nt + t];
+      if (gbc != nullptr) gbc[o] = (float)sum;
+    }
+  }
+}
+
 template <int CI>
 __global__ __launch_bounds__(kThreads) void pointwise_mlp2_kernel(
     int Ci, int H, int Co, long long np, const float* __restrict__ x, const float* __restrict__ W1,
@@ -2728,6 +2831,34 @@ hipError_t launch_time_lift(int B, int Ci, int Co, int64_t np, int Nt, const flo
   else
     hipLaunchKernelGGL((time_lift_kernel<32>), grid, dim3(kThreads), 0, s, Ci, Co, (long long)np, Nt, a, wt,
                        bt, wc, bc, out);
+  return hipGetLastError();
+}
+
+size_t time_lift_bwd_workspace_bytes(int Ci, int Co, int Nt) {
+  return ((size_t)kLiftChunks + 1) * (size_t)(Ci + 1) * Co * Nt * sizeof(double);
+}
+
+hipError_t launch_time_lift_bwd(int B, int Ci, int Co, int64_t S, int Nt, const float* a, const float* wt,
+                                const float* bt, const float* wc, const float* g, float* gwt, float* gbt,
+                                float* gwc, float* gbc, void* ws, hipStream_t s) {
+  if (Ci > 8 || B > kLiftChunks || S <= 0) return hipErrorInvalidValue;
+  const int npair = Co * Nt, nent = (Ci + 1) * npair;
+  int cpb = (int)((S + 511) / 512);               // chunks per batch entry: at least 512 positions each
+  if (cpb > kLiftChunks / B) cpb = kLiftChunks / B;
+  if (cpb < 1) cpb = 1;
+  const int nchunk = B * cpb;
+  double* part = static_cast<double*>(ws);
+  double* G = part + (size_t)kLiftChunks * nent;
+  const dim3 grid((unsigned)((npair + kThreads - 1) / kThreads), (unsigned)nchunk);
+#define FNO_TLB(CIV)                                                                                        \
+  hipLaunchKernelGGL((time_lift_bwd_kernel<CIV>), grid, dim3(kThreads), 0, s, Ci, Co, (long long)S, Nt, cpb, \
+                     a, g, part)
+  if (Ci == 1) FNO_TLB(1); else if (Ci == 2) FNO_TLB(2); else if (Ci <= 4) FNO_TLB(4); else FNO_TLB(8);
+#undef FNO_TLB
+  hipLaunchKernelGGL(time_lift_bwd_reduce_kernel, dim3((nent + kThreads - 1) / kThreads), dim3(kThreads), 0, s,
+                     part, nchunk, nent, G);
+  hipLaunchKernelGGL(time_lift_bwd_final_kernel, dim3(1), dim3(kThreads), 0, s, Ci, Co, Nt, G, wt, bt, wc, gwt,
+                     gbt, gwc, gbc);
   return hipGetLastError();
 }
 

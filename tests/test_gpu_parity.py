@@ -330,6 +330,45 @@ def test_time_lift_matches_oracle(shape):
     assert rel(host(out), O.time_lift(a, wt, np.zeros(nt), wc, np.zeros(c_out))) <= TOL
 
 
+@pytest.mark.parametrize("shape", [
+    # batch, c_in, c_out, spatial grid, nt
+    (2, 2, 20, (6, 5, 4), 30),        # the paper's two input channels, one chunk per batch entry
+    (1, 3, 8, (4, 4, 8), 16),         # three input channels on the four-channel register tile
+    (3, 1, 24, (3, 2, 5), 7),         # odd nt, one input channel, pairs that do not fill the last block
+    (1, 5, 4, (7, 9, 11), 4),         # five input channels, a ragged tail of positions
+    (1, 2, 20, (60, 60, 64), 30),     # a training sample of the paper (Sec. 4), full size: 450 chunks
+])
+def test_time_lift_adjoint_matches_oracle(shape):
+    batch, c_in, c_out, grid, nt = shape
+    rng = np.random.default_rng([23, batch, c_in, c_out, nt])
+    a = rng.standard_normal((batch, c_in) + grid + (1,)).astype(np.float32)
+    wt = rng.standard_normal(nt).astype(np.float32)
+    bt = rng.standard_normal(nt).astype(np.float32)
+    wc = (rng.standard_normal((c_out, c_in)) / np.sqrt(c_in)).astype(np.float32)
+    g = rng.standard_normal((batch, c_out) + grid + (nt,)).astype(np.float32)
+    nspace = int(np.prod(grid))
+    ws = torch.empty(B.fno_time_lift_bwd_workspace_bytes(c_in, c_out, nt) // 4 + 2, dtype=torch.float32,
+                     device="cuda")
+    gwt, gbt = torch.empty(nt, device="cuda"), torch.empty(nt, device="cuda")
+    gwc, gbc = torch.empty((c_out, c_in), device="cuda"), torch.empty(c_out, device="cuda")
+    B.fno_time_lift_bwd(batch, c_in, c_out, nspace, nt, dev(a), dev(wt), dev(bt), dev(wc), dev(g),
+                        gwt, gbt, gwc, gbc, ws)
+    torch.cuda.synchronize()
+    want = O.time_lift_bwd(a, wt, bt, wc, g)
+    for name, got in (("gWt", gwt), ("gbt", gbt), ("gWc", gwc), ("gbc", gbc)):
+        assert rel(host(got), want[name]) <= TOL, name
+    # same bits on a second run; without the time bias; a subset of the outputs
+    gwt2, gwc2 = torch.empty_like(gwt), torch.empty_like(gwc)
+    B.fno_time_lift_bwd(batch, c_in, c_out, nspace, nt, dev(a), dev(wt), dev(bt), dev(wc), dev(g),
+                        gwt2, None, gwc2, None, ws)
+    torch.cuda.synchronize()
+    assert torch.equal(gwt, gwt2) and torch.equal(gwc, gwc2)
+    B.fno_time_lift_bwd(batch, c_in, c_out, nspace, nt, dev(a), dev(wt), None, dev(wc), dev(g),
+                        None, None, gwc2, None, ws)
+    torch.cuda.synchronize()
+    assert rel(host(gwc2), O.time_lift_bwd(a, wt, np.zeros(nt), wc, g)["gWc"]) <= TOL
+
+
 @pytest.mark.parametrize("n", [7, 100003, 60 * 60 * 64 * 30])
 def test_relative_l2_loss_and_gradient_match_oracle(n):
     rng = np.random.default_rng([11, n])
