@@ -2244,14 +2244,24 @@ __global__ __launch_bounds__(kThreads) void time_lift_bwd_kernel(
   }
 }
 
-// G[k][pair] = sum over the chunks, in order
+// G[k][pair] = sum over the chunks: 32 entries per block, the chunks dealt to 8 thread groups whose
+// sums are added in a fixed order
 __global__ __launch_bounds__(kThreads) void time_lift_bwd_reduce_kernel(const double* __restrict__ part, int nchunk,
                                                                         int nent, double* __restrict__ G) {
-  const int e = blockIdx.x * kThreads + threadIdx.x;
-  if (e >= nent) return;
+  __shared__ double P[8][32];
+  const int el = threadIdx.x & 31, grp = threadIdx.x >> 5;
+  const int e = blockIdx.x * 32 + el;
   double sum = 0.0;
-  for (int c = 0; c < nchunk; ++c) sum += part[(long long)c * nent + e];
-  G[e] = sum;
+  if (e < nent)
+    for (int c = grp; c < nchunk; c += 8) sum += part[(long long)c * nent + e];
+  P[grp][el] = sum;
+  __syncthreads();
+  if (grp == 0 && e < nent) {
+    double tot = 0.0;
+#pragma unroll
+    for (int k = 0; k < 8; ++k) tot += P[k][el];
+    G[e] = tot;
+  }
 }
 
 // the four small contractions, one output per thread
@@ -2855,8 +2865,8 @@ hipError_t launch_time_lift_bwd(int B, int Ci, int Co, int64_t S, int Nt, const 
                      a, g, part)
   if (Ci == 1) FNO_TLB(1); else if (Ci == 2) FNO_TLB(2); else if (Ci <= 4) FNO_TLB(4); else FNO_TLB(8);
 #undef FNO_TLB
-  hipLaunchKernelGGL(time_lift_bwd_reduce_kernel, dim3((nent + kThreads - 1) / kThreads), dim3(kThreads), 0, s,
-                     part, nchunk, nent, G);
+  hipLaunchKernelGGL(time_lift_bwd_reduce_kernel, dim3((nent + 31) / 32), dim3(kThreads), 0, s, part, nchunk,
+                     nent, G);
   hipLaunchKernelGGL(time_lift_bwd_final_kernel, dim3(1), dim3(kThreads), 0, s, Ci, Co, Nt, G, wt, bt, wc, gwt,
                      gbt, gwc, gbc);
   return hipGetLastError();
