@@ -557,3 +557,64 @@ def test_whole_network_training_step_matches_oracle():
         torch.cuda.synchronize()
         po, _, _ = O.adam_step(p_host.astype(np.float64).ravel(), np.asarray(g_ref).ravel(), np.zeros(n), np.zeros(n), 1)
         assert rel(host(p).ravel(), po) <= TOL
+
+
+def test_network_with_time_lift_training_gradients_match_oracle():
+    """The paper's input stage (eqs. (8)-(9)) in front of the network: time + channel lift of an
+    input without a time axis, one block, projection, relative L2 loss, and the gradients of all
+    four lift parameters through the whole chain."""
+    sgrid, nt, modes, c_in, width, hidden = (6, 4, 8), 8, (2, 2, 2, 3), 2, 8, 32
+    grid = sgrid + (nt,)
+    spec = O.LayerSpec(grid, modes, 0)
+    counts = tuple(len(k) for k in O.mode_lists(spec))
+    nspace, npts = int(np.prod(sgrid)), int(np.prod(grid))
+    rng = np.random.default_rng(41)
+    a = rng.standard_normal((1, c_in) + sgrid + (1,)).astype(np.float32)
+    wt, bt = rng.standard_normal(nt).astype(np.float32), (0.3 * rng.standard_normal(nt)).astype(np.float32)
+    wc = (rng.standard_normal((width, c_in)) / np.sqrt(c_in)).astype(np.float32)
+    bc = (0.1 * rng.standard_normal(width)).astype(np.float32)
+    y = synth.normal_field(1, synth.T_TARGET, 1, 1, grid)
+    R, W, b = (synth.spectral_weights(3, width, width, counts), synth.linear_weights(13, width, width),
+               synth.bias(13, width))
+    w1, b1 = synth.linear_weights(1, hidden, width, synth.T_PROJ), synth.bias(1, hidden, synth.T_PROJ)
+    w2, b2 = synth.linear_weights(2, 1, hidden, synth.T_PROJ), synth.bias(2, 1, synth.T_PROJ)
+
+    desc = B.make_desc(1, width, width, grid, modes, 0, B.FNO_ACT_GELU)
+    ws = B.alloc_workspace(desc, B.FNO_OP_BLOCK_BWD)
+    d = {k: dev(v) for k, v in dict(a=a, wt=wt, bt=bt, wc=wc, bc=bc, y=y, R=R, W=W, b=b, w1=w1, b1=b1, w2=w2,
+                                    b2=b2).items()}
+    v0 = torch.empty((1, width) + grid, device="cuda")
+    B.fno_time_lift(1, c_in, width, nspace, nt, d["a"], d["wt"], d["bt"], d["wc"], d["bc"], v0)
+    v1, z = torch.empty_like(v0), torch.empty_like(v0)
+    xh = torch.empty((1, width) + counts, dtype=torch.complex64, device="cuda")
+    B.fno_block_fwd(desc, v0, d["R"], d["W"], d["b"], v1, z, xh, ws)
+    u = torch.empty((1, 1) + grid, device="cuda")
+    B.fno_pointwise_mlp2(1, width, hidden, 1, npts, v1, d["w1"], d["b1"], d["w2"], d["b2"], u)
+    lws = torch.empty(B.fno_rel_l2_workspace_bytes() // 4, dtype=torch.float32, device="cuda")
+    loss, gu = torch.empty(1, device="cuda"), torch.empty_like(u)
+    B.fno_rel_l2_loss(npts, u, d["y"], loss, gu, lws)
+    pws = torch.empty(B.fno_pointwise_bwd_workspace_bytes(width, hidden, 1) // 4 + 2, dtype=torch.float32,
+                      device="cuda")
+    gv1, gv0 = torch.empty_like(v0), torch.empty_like(v0)
+    B.fno_pointwise_mlp2_bwd(1, width, hidden, 1, npts, v1, d["w1"], d["b1"], d["w2"], gu, gv1,
+                             None, None, None, None, pws)
+    B.fno_block_bwd(desc, v0, d["R"], d["W"], z, xh, gv1, gv0, torch.empty_like(d["R"]), torch.empty_like(d["W"]),
+                    torch.empty_like(d["b"]), ws)
+    tws = torch.empty(B.fno_time_lift_bwd_workspace_bytes(c_in, width, nt) // 4 + 2, dtype=torch.float32,
+                      device="cuda")
+    gwt, gbt = torch.empty(nt, device="cuda"), torch.empty(nt, device="cuda")
+    gwc, gbc = torch.empty((width, c_in), device="cuda"), torch.empty(width, device="cuda")
+    B.fno_time_lift_bwd(1, c_in, width, nspace, nt, d["a"], d["wt"], d["bt"], d["wc"], gv0, gwt, gbt, gwc, gbc, tws)
+    torch.cuda.synchronize()
+
+    # oracle: the same chain in float64
+    v0o = O.time_lift(a, wt, bt, wc, bc)
+    v1o = O.block_fwd(v0o, R, W, b, spec, "gelu")[0]
+    uo = O.pointwise_mlp2(v1o, w1, b1, w2, b2)
+    assert rel(host(v0), v0o) <= TOL and rel(host(u), uo) <= TOL
+    gvo = O.pointwise_mlp2_bwd(v1o, w1, b1, w2, O.rel_l2_grad(uo, y))["gx"]
+    gvo = O.block_bwd(v0o, R, W, b, gvo, spec, "gelu")["gx"]
+    ref = O.time_lift_bwd(a, wt, bt, wc, gvo)
+    GT = 5 * TOL
+    for name, got in (("gWt", gwt), ("gbt", gbt), ("gWc", gwc), ("gbc", gbc)):
+        assert rel(host(got), ref[name]) <= GT, name
