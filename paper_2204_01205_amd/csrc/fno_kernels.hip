@@ -122,9 +122,22 @@ __global__ __launch_bounds__(kThreads) void tz_fwd_kernel(
 
   // 1. coalesced load of the planes
   const float* src = x + plane0 * plane_elems;
-  for (int idx = tid; idx < np * plane_elems; idx += kThreads) {
-    const int row = idx / Nt, t = idx - row * Nt;
-    S[row * sS + t] = src[idx];
+  const int nelem = np * plane_elems;
+  for (int i0 = tid; i0 < nelem; i0 += 8 * kThreads) {     // eight loads in flight per thread
+    float v[8];
+#pragma unroll
+    for (int u = 0; u < 8; ++u) {
+      const int idx = i0 + u * kThreads;
+      v[u] = idx < nelem ? src[idx] : 0.f;
+    }
+#pragma unroll
+    for (int u = 0; u < 8; ++u) {
+      const int idx = i0 + u * kThreads;
+      if (idx < nelem) {
+        const int row = idx / Nt, t = idx - row * Nt;
+        S[row * sS + t] = v[u];
+      }
+    }
   }
   __syncthreads();
 
