@@ -1446,19 +1446,37 @@ __global__ __launch_bounds__(kThreads) void bwd_pointwise_kernel(
     const long long b = tile / tiles_per_b;
     const long long p = (tile % tiles_per_b) * kBwdTile + tid;
     const bool live = p < N;
-    for (int o = 0; o < Co; ++o) {
-      float gv = 0.f;
-      if (live) {
-        const long long e = (b * Co + o) * N + p;
-        const float zv = (act || mse_target) ? z[e] : 0.f;
-        float g = gout[e];
-        if (mse_target) g = mse_scale * ((act ? gelu_f(zv) : zv) - g);
-        gv = act ? g * gelu_prime_f(zv) : g;
-        if (gz_out != nullptr) gz_out[e] = gv;
+    for (int o0 = 0; o0 < Co; o0 += 8) {          // eight channels per pass: their loads go out together
+      float zv[8], g[8];
+#pragma unroll
+      for (int u = 0; u < 8; ++u) {
+        const bool on = live && o0 + u < Co;
+        const long long e = (b * Co + o0 + u) * N + p;
+        zv[u] = (on && (act || mse_target)) ? z[e] : 0.f;
+        g[u] = on ? gout[e] : 0.f;
       }
-      Gs[o * sR + tid] = gv;
+#pragma unroll
+      for (int u = 0; u < 8; ++u) {
+        if (o0 + u < Co) {
+          float gv = 0.f;
+          if (live) {
+            float gg = g[u];
+            if (mse_target) gg = mse_scale * ((act ? gelu_f(zv[u]) : zv[u]) - gg);
+            gv = act ? gg * gelu_prime_f(zv[u]) : gg;
+            if (gz_out != nullptr) gz_out[(b * Co + o0 + u) * N + p] = gv;
+          }
+          Gs[(o0 + u) * sR + tid] = gv;
+        }
+      }
     }
-    for (int i = 0; i < Ci; ++i) Xs[i * sR + tid] = live ? x[(b * Ci + i) * N + p] : 0.f;
+    for (int i0 = 0; i0 < Ci; i0 += 8) {
+      float xv[8];
+#pragma unroll
+      for (int u = 0; u < 8; ++u) xv[u] = (live && i0 + u < Ci) ? x[(b * Ci + i0 + u) * N + p] : 0.f;
+#pragma unroll
+      for (int u = 0; u < 8; ++u)
+        if (i0 + u < Ci) Xs[(i0 + u) * sR + tid] = xv[u];
+    }
     __syncthreads();
 #pragma unroll
     for (int h = 0; h < kBwdPairs; ++h) {
@@ -1468,10 +1486,26 @@ __global__ __launch_bounds__(kThreads) void bwd_pointwise_kernel(
         if (q < Co * Ci) {
           const float* gr = Gs + (q / Ci) * sR;
           const float* xr = Xs + (q % Ci) * sR;
-          for (int t = 0; t < kBwdTile; ++t) s = fmaf(gr[t], xr[t], s);
+          float s1 = 0.f;
+          for (int t = 0; t < kBwdTile; t += 8) {    // eight terms per pass: their LDS reads go out together
+            float gq[8], xq[8];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) { gq[u] = gr[t + u]; xq[u] = xr[t + u]; }
+#pragma unroll
+            for (int u = 0; u < 8; u += 2) { s = fmaf(gq[u], xq[u], s); s1 = fmaf(gq[u + 1], xq[u + 1], s1); }
+          }
+          s += s1;
         } else {
           const float* gr = Gs + (q - Co * Ci) * sR;
-          for (int t = 0; t < kBwdTile; ++t) s += gr[t];
+          float s1 = 0.f;
+          for (int t = 0; t < kBwdTile; t += 8) {
+            float gq[8];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) gq[u] = gr[t + u];
+#pragma unroll
+            for (int u = 0; u < 8; u += 2) { s += gq[u]; s1 += gq[u + 1]; }
+          }
+          s += s1;
         }
         acc[h] += double(s);
       }
@@ -1799,24 +1833,6 @@ constexpr int kMlpXS = kMlpTile + 1;     // row stride of the staged tile (odd: 
 constexpr int kMlpTS = 33;               // row stride of a wave's 32x32 turn buffer
 constexpr int kMlpFlush = 16;            // passes between flushes of the fp32 weight-gradient accumulator
 
-// gelu(z) and its derivative Phi(z) + z phi(z), with the branch-free erf of gelu_fast_f
-__device__ __forceinline__ void gelu_and_slope(float z, float& a, float& d) {
-  const float az = fabsf(z);
-  const float x = az * 0.70710678118654752440f;
-  float p = fmaf(x, 0.0000430638f, 0.0002765672f);
-  p = fmaf(x, p, 0.0001520143f);
-  p = fmaf(x, p, 0.0092705272f);
-  p = fmaf(x, p, 0.0422820123f);
-  p = fmaf(x, p, 0.0705230784f);
-  p = fmaf(x, p, 1.0f);
-  p = p * p; p = p * p; p = p * p; p = p * p;
-  const float erfx = 1.0f - __builtin_amdgcn_rcpf(p);
-  a = 0.5f * fmaf(az, erfx, z);
-  const float cdf = fmaf(0.5f, copysignf(erfx, z), 0.5f);
-  const float pdf = 0.39894228040143267794f * __expf(-0.5f * z * z);
-  d = fmaf(z, pdf, cdf);
-}
-
 template <int KS, int CO>
 __global__ __launch_bounds__(512) void mlp2_fwd_mfma_kernel(
     int B, int Ci, int H, int Co, long long N, const float* __restrict__ x, const float* __restrict__ W1,
@@ -1996,7 +2012,7 @@ __global__ __launch_bounds__(512) void mlp2_bwd_mfma_kernel(
 #pragma unroll
       for (int v = 0; v < 16; ++v) {
         float a, d;
-        gelu_and_slope(hacc[v], a, d);
+        gelu_and_grad_f(hacc[v], a, d);
         float tt = 0.f;
 #pragma unroll
         for (int o = 0; o < CO; ++o) {
