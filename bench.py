@@ -28,6 +28,8 @@ def parse():
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--config", default="cfg4", help="workload name from synth.CONFIGS (block forward; cfg5: forward + backward), or time_lift, time_lift_bwd")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--forward-only", action="store_true",
+                    help="with --network: the forward pass alone (lift, blocks, projection), nothing saved")
     ap.add_argument("--network", action="store_true",
                     help="time one training step of the whole network of the workload (cfg3: lift, blocks, "
                          "projection, relative L2 loss, backward, Adam) instead of one block")
@@ -164,7 +166,15 @@ def network_step_bench(args, torch, B, synth):
     gblk = [tuple(grads[6 + 3 * k: 9 + 3 * k]) for k in range(nblocks)]
     state = {"step": 0}
 
+    def forward():
+        B.fno_pointwise_linear(batch, c_in, width, npts, a, lw, lb, vs[0])
+        for k, (R, W, b) in enumerate(blocks):
+            B.fno_block_fwd(desc, vs[k & 1], R, W, b, vs[(k + 1) & 1], None, None, ws)
+        B.fno_pointwise_mlp2(batch, width, hidden, 1, npts, vs[nblocks & 1], w1, b1, w2, b2, u)
+
     def step():
+        if args.forward_only:
+            return forward()
         state["step"] += 1
         B.fno_pointwise_linear(batch, c_in, width, npts, a, lw, lb, vs[0])
         for k, (R, W, b) in enumerate(blocks):
@@ -195,12 +205,13 @@ def network_step_bench(args, torch, B, synth):
         "value": nblocks * pc / (ms * 1e-3) / 1e9, "unit": "Gpoint-channels/s", "n_gpus": 1, "steps": args.steps,
         "warmup": args.warmup, "ms_per_step": ms, "higher_is_better": True, "scaling": "weak",
         "vs_baseline": None, "dtype": "f32", "data": "synthetic",
-        "config": {"workload": f"{args.config} network training step: lift {c_in}->{width}, {nblocks} blocks, projection "
-                               f"{width}->{hidden}->1, relative L2 loss, backward, Adam; batch {batch}, grid "
+        "config": {"workload": f"{args.config} network {'forward' if args.forward_only else 'training step'}: lift "
+                               f"{c_in}->{width}, {nblocks} blocks, projection {width}->{hidden}->1"
+                               f"{'' if args.forward_only else ', relative L2 loss, backward, Adam'}; batch {batch}, grid "
                                f"{grid[0]}x{grid[1]}x{grid[2]}x{grid[3]}; value counts the point-channels of the "
                                f"{nblocks} blocks once per step",
                    "global_batch": batch, "parallelism": "single GPU"},
-        "loss": float(loss.cpu()),
+        "loss": None if args.forward_only else float(loss.cpu()),
     }))
 
 
