@@ -453,6 +453,9 @@ def test_pointwise_adjoints_match_oracle(shape):
     B.fno_pointwise_mlp2(batch, c_in, hidden, c_out, npts, dev(x), dev(w1), dev(b1), dev(w2), dev(b2), u)
     torch.cuda.synchronize()
     assert rel(host(u), O.pointwise_mlp2(x, w1, b1, w2, b2)) <= TOL
+    B.fno_pointwise_mlp2(batch, c_in, hidden, c_out, npts, dev(x), dev(w1), None, dev(w2), None, u)
+    torch.cuda.synchronize()
+    assert rel(host(u), O.pointwise_mlp2(x, w1, np.zeros(hidden), w2, np.zeros(c_out))) <= TOL
     gW1 = torch.empty((hidden, c_in), device="cuda")
     gb1 = torch.empty(hidden, device="cuda")
     gW2 = torch.empty((c_out, hidden), device="cuda")
@@ -469,6 +472,13 @@ def test_pointwise_adjoints_match_oracle(shape):
                              None, gW1b, None, gW2b, None, ws)
     torch.cuda.synchronize()
     assert torch.equal(gW1, gW1b) and torch.equal(gW2, gW2b)
+    # without the hidden bias
+    B.fno_pointwise_mlp2_bwd(batch, c_in, hidden, c_out, npts, dev(x), dev(w1), None, dev(w2), dev(gu),
+                             gx, gW1b, gb1, gW2b, gb2, ws)
+    torch.cuda.synchronize()
+    want0 = O.pointwise_mlp2_bwd(x, w1, np.zeros(hidden), w2, gu)
+    for name, got in (("gx", gx), ("gW1", gW1b), ("gb1", gb1), ("gW2", gW2b), ("gb2", gb2)):
+        assert rel(host(got), want0[name]) <= TOL, name
 
 
 def test_whole_network_training_step_matches_oracle():
