@@ -228,11 +228,13 @@ __host__ __device__ inline int tzd_row_stride(int Nz) { return Nz + ((20 - (Nz &
 
 __global__ __launch_bounds__(kThreads) void tz_fwd_dense_kernel(
     const float* __restrict__ x, float2* __restrict__ out, const float2* __restrict__ twt,
-    const float2* __restrict__ twz, long long planes, int Nz, int Nt, int Lz, int mt, int ppb) {
+    const float2* __restrict__ twz, long long planes, int Nz, int Nt, int Lz, int mt, int ppb, int alias) {
   HIP_DYNAMIC_SHARED(float, smem)
   const int sT = tzd_row_stride(Nz);
   float2* T = reinterpret_cast<float2*>(smem);                 // [16][sT]
-  float2* P = T + 16 * sT;                                     // [4][kDenseMT * 16][16]
+  // [4][kDenseMT * 16][16] partial sums; when one sweep covers all kept z-frequencies they take
+  // T's place once the sweep has read it (alias = 1), which halves the block's LDS
+  float2* P = alias ? T : T + 16 * sT;
   const int tid = threadIdx.x, w = tid >> 6, lane = tid & 63, lr = lane & 15, lk = lane >> 4;
   const long long plane0 = (long long)blockIdx.x * ppb;
   const int np = (int)min((long long)ppb, planes - plane0);
@@ -297,6 +299,7 @@ __global__ __launch_bounds__(kThreads) void tz_fwd_dense_kernel(
           im[m] = __builtin_amdgcn_mfma_f32_16x16x4f32(av[u][m].y, bv[u].x, im[m], 0, 0, 0);
         }
     }
+    if (alias) __syncthreads();                          // every wave is done reading T
 #pragma unroll
     for (int m = 0; m < kDenseMT; ++m)
 #pragma unroll
@@ -2486,12 +2489,15 @@ hipError_t launch_tz_fwd(const float* x, float2* out, const float2* twt, const f
   }
   if (az.M == 1 && Nt % 4 == 0 && mt <= 16 && (reinterpret_cast<uintptr_t>(x) & 15) == 0) {
     const int ppb = 16 / mt;
-    const size_t lds = (size_t)16 * tzd_row_stride(az.N) * 8 + (size_t)(kThreads / 64) * kDenseMT * 16 * 16 * 8;
+    const size_t t_bytes = (size_t)16 * tzd_row_stride(az.N) * 8;
+    const size_t p_bytes = (size_t)(kThreads / 64) * kDenseMT * 16 * 16 * 8;
+    const int alias = az.L <= kDenseMT * 16;      // one sweep: the partial sums reuse the rows' LDS
+    const size_t lds = alias ? (t_bytes > p_bytes ? t_bytes : p_bytes) : t_bytes + p_bytes;
     const int64_t nblk = (planes + ppb - 1) / ppb;
     if (nblk > 0x7fffffffLL) return hipErrorInvalidValue;
     if (lds <= (size_t)(150 * 1024)) {
       hipLaunchKernelGGL(tz_fwd_dense_kernel, dim3((unsigned)nblk), dim3(kThreads), lds, s, x, out, twt, twz,
-                         (long long)planes, az.N, Nt, az.L, mt, ppb);
+                         (long long)planes, az.N, Nt, az.L, mt, ppb, alias);
       return hipGetLastError();
     }
   }
