@@ -704,6 +704,12 @@ __device__ __forceinline__ void zt_epilogue_point(const EpiArgs& ep, int Co, con
   }
 }
 
+// The t stage can hold a block's results in registers (eight 16-row tiles per wave, one 16-wide
+// tile of t) until every wave has read V, and then write Y over V: one LDS buffer instead of two.
+__host__ __device__ inline bool zt_y_over_v(int Nt, int rows, int mt) {
+  return Nt <= 16 && rows <= 512 && 2 * mt <= 36;
+}
+
 template <int MZ, int CO, bool EXACT>
 __global__ __launch_bounds__(kThreads) void zt_inv_kernel(
     const float2* __restrict__ a, float* __restrict__ out, const float2* __restrict__ twt,
@@ -715,8 +721,10 @@ __global__ __launch_bounds__(kThreads) void zt_inv_kernel(
   const int Rz = Q * MZ;
   const int sY = Nt + 1;
   float2* V = reinterpret_cast<float2*>(smem);                 // [Co][Rz][mt]
-  float* Y = smem + 2 * Co * Rz * mt;                          // [Co][Rz][sY]
-  float* WS = Y + ((Co * Rz * sY + 3) & ~3);                   // [Cu][CO]: W of the epilogue, zero past Co
+  const bool y_over_v = zt_y_over_v(Nt, Co * Rz, mt);
+  float* Y = y_over_v ? smem : smem + 2 * Co * Rz * mt;        // [Co][Rz][sY]
+  const int vy_floats = y_over_v ? max(2 * Co * Rz * mt, Co * Rz * sY) : 2 * Co * Rz * mt + Co * Rz * sY;
+  float* WS = smem + ((vy_floats + 3) & ~3);                   // [Cu][CO]: W of the epilogue, zero past Co
   const int tid = threadIdx.x;
   if (ep.u != nullptr && ep.Cu <= CO)
     for (int idx = tid; idx < ep.Cu * CO; idx += kThreads) {
@@ -821,6 +829,44 @@ __global__ __launch_bounds__(kThreads) void zt_inv_kernel(
     const int K2 = 2 * mt, kst = (K2 + 3) >> 2;
     const int nrows = Co * Rz;
     const int nrt = (nrows + 15) >> 4, ntt = (Nt + 15) >> 4;
+    if (y_over_v) {
+      const int t = lr;
+      float bt[kTSteps];
+#pragma unroll
+      for (int s = 0; s < kTSteps; ++s) {
+        const int kk = 4 * s + lk;
+        bt[s] = (kk < K2 && t < Nt) ? twf[((kk >> 1) * Nt + t) * 2 + (kk & 1)] : 0.f;
+      }
+      v4f accs[8];
+#pragma unroll
+      for (int k = 0; k < 8; ++k) {
+        const int rt = wv_id + (kThreads / 64) * k;
+        accs[k] = v4f{0.f, 0.f, 0.f, 0.f};
+        if (rt < nrt) {
+          const int row = rt * 16 + lr;
+#pragma unroll
+          for (int s = 0; s < kTSteps; ++s) {
+            if (s < kst) {
+              const int kk = 4 * s + lk;
+              const float av = (row < nrows && kk < K2) ? Vf[row * K2 + kk] : 0.f;
+              accs[k] = __builtin_amdgcn_mfma_f32_16x16x4f32(av, bt[s], accs[k], 0, 0, 0);
+            }
+          }
+        }
+      }
+      __syncthreads();                           // every wave has read its rows of V
+#pragma unroll
+      for (int k = 0; k < 8; ++k) {
+        const int rt = wv_id + (kThreads / 64) * k;
+        if (rt < nrt) {
+#pragma unroll
+          for (int v = 0; v < 4; ++v) {
+            const int r2 = rt * 16 + 4 * lk + v;
+            if (r2 < nrows && t < Nt) Y[r2 * sY + t] = accs[k][v];
+          }
+        }
+      }
+    } else
     for (int tt = 0; tt < ntt; ++tt) {
       const int t = tt * 16 + lr;
       float bt[kTSteps];
@@ -2377,9 +2423,11 @@ size_t tz_fwd_lds(AxisPlan az, int Nt, int mt, int ppb) {
 
 size_t zt_inv_lds(AxisPlan az, int Nt, int mt, int Co) {
   const int Rz = pick_q(az, Nt) * az.M;
-  // V, Y (rounded up to 16 bytes), and the epilogue's weights for up to kMaxCo x kMaxCo channels
-  return (size_t)Co * Rz * (size_t)mt * 8 + (((size_t)Co * Rz * (Nt + 1) + 3) & ~(size_t)3) * 4 +
-         (size_t)kMaxCo * kMaxCo * 4;
+  // V and Y (one buffer where Y may take V's place), rounded up to 16 bytes, and the epilogue's
+  // weights for up to kMaxCo x kMaxCo channels
+  const size_t v_floats = (size_t)2 * Co * Rz * mt, y_floats = (size_t)Co * Rz * (Nt + 1);
+  const size_t vy = zt_y_over_v(Nt, Co * Rz, mt) ? (v_floats > y_floats ? v_floats : y_floats) : v_floats + y_floats;
+  return ((vy + 3) & ~(size_t)3) * 4 + (size_t)kMaxCo * kMaxCo * 4;
 }
 
 int axis_cols(AxisPlan ax, int64_t inner, int rows, int wmax) {
