@@ -522,9 +522,19 @@ __global__ __launch_bounds__(kThreads) void axis_inv_kernel(
 
   if (tw_lds)
     for (int idx = tid; idx < L * P; idx += nthr) TWs[idx] = tw[idx];
-  for (int idx = tid; idx < L * W; idx += nthr) {
-    const int col = idx % W, j = idx / W;
-    if (col < wc) Y[idx] = in[(o * L + j) * inner + c0 + col];
+  for (int i0 = tid; i0 < L * W; i0 += 8 * nthr) {         // eight loads in flight per thread
+    float2 v[8];
+#pragma unroll
+    for (int u = 0; u < 8; ++u) {
+      const int idx = i0 + u * nthr;
+      const int col = idx % W, j = idx / W;
+      v[u] = (idx < L * W && col < wc) ? in[(o * L + j) * inner + c0 + col] : make_float2(0.f, 0.f);
+    }
+#pragma unroll
+    for (int u = 0; u < 8; ++u) {
+      const int idx = i0 + u * nthr;
+      if (idx < L * W && idx % W < wc) Y[idx] = v[u];
+    }
   }
   __syncthreads();
   for (int idx = tid; idx < P * W; idx += nthr) {
