@@ -1987,13 +1987,16 @@ __global__ __launch_bounds__(512) void mlp2_bwd_mfma_kernel(
   float* GS = XS + 32 * kMlpXS;                          // [CO][kMlpTile] upstream gradient of the tile
   float* T = GS + CO * kMlpTile + w * (32 * kMlpTS);     // this wave's [32][kMlpTS] turn buffer
   float* GXP = GS + CO * kMlpTile + nw * (32 * kMlpTS);  // [nw][Ci][kMlpXS] partial gx of the waves
-  int acc_off = 32 * kMlpXS + CO * kMlpTile + nw * (32 * kMlpTS) + nw * Ci * kMlpXS;
+  float* W2S = GXP + nw * Ci * kMlpXS;                   // [CO][H], only when CO > 1 (else W2 sits in registers)
+  int acc_off = 32 * kMlpXS + CO * kMlpTile + nw * (32 * kMlpTS) + nw * Ci * kMlpXS + (CO > 1 ? CO * H : 0);
   acc_off += acc_off & 1;
   double* ACC = reinterpret_cast<double*>(smem + acc_off);   // [nsum] gW1 | gb1 | gW2 | gb2
   const int nsum = H * (Ci + 1) + Co * H + Co;
   for (int q = tid; q < nsum; q += nthreads) ACC[q] = 0.0;
   for (int e = tid; e < (32 - Ci) * kMlpXS; e += nthreads) XS[Ci * kMlpXS + e] = e < kMlpXS ? 1.f : 0.f;
-  float A1[KS], A2[16], W2r[CO][16];
+  if constexpr (CO > 1)
+    for (int e = tid; e < CO * H; e += nthreads) W2S[e] = e < Co * H ? W2[e] : 0.f;
+  float A1[KS], A2[16], W2r[1][16];
 #pragma unroll
   for (int s = 0; s < KS; ++s) {
     const int i = 2 * s + half, k = w * 32 + c;
@@ -2003,8 +2006,7 @@ __global__ __launch_bounds__(512) void mlp2_bwd_mfma_kernel(
   for (int v = 0; v < 16; ++v) {
     const int k = w * 32 + mfma_row(v, half);
     A2[v] = c < Ci ? W1[k * Ci + c] : 0.f;
-#pragma unroll
-    for (int o = 0; o < CO; ++o) W2r[o][v] = o < Co ? W2[o * H + k] : 0.f;
+    if constexpr (CO == 1) W2r[0][v] = W2[k];
   }
   const long long tiles_per_b = (N + kMlpTile - 1) / kMlpTile;
   const long long ntiles = tiles_per_b * B;
@@ -2075,7 +2077,8 @@ __global__ __launch_bounds__(512) void mlp2_bwd_mfma_kernel(
         float tt = 0.f;
 #pragma unroll
         for (int o = 0; o < CO; ++o) {
-          tt = fmaf(W2r[o][v], gl[o], tt);
+          const float w2v = CO == 1 ? W2r[0][v] : W2S[o * H + w * 32 + mfma_row(v, half)];
+          tt = fmaf(w2v, gl[o], tt);
           acc2[o][v] = fmaf(gl[o], a, acc2[o][v]);
         }
         gh[v] = tt * d;
@@ -2882,6 +2885,7 @@ bool mlp2_mfma_fits(int Ci, int H, int Co) {
 size_t mlp2_bwd_mfma_lds(int Ci, int H, int Co) {
   const int nw = H / 32, co = Co == 1 ? 1 : 4;
   size_t floats = (size_t)32 * kMlpXS + (size_t)co * kMlpTile + (size_t)nw * 32 * kMlpTS + (size_t)nw * Ci * kMlpXS;
+  if (co > 1) floats += (size_t)co * H;
   floats += floats & 1;
   return floats * 4 + ((size_t)H * (Ci + 1) + (size_t)Co * H + Co) * 8;
 }
