@@ -197,6 +197,21 @@ int fno_pointwise_mlp2(int32_t batch, int32_t c_in, int32_t hidden, int32_t c_ou
                        const float* x, const float* W1, const float* b1, const float* W2,
                        const float* b2, float* y, void* stream);
 
+/* For callers that cannot allocate device memory or bring a workspace (code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc): fno_spectral_conv_fwd with the
+ * workspace taken from a fixed array of FNO_STATIC_SCRATCH_BYTES bytes of device memory that the
+ * library owns (one copy per GPU it runs on, held until the process ends).  Arguments, layout,
+ * results and error codes are those of fno_spectral_conv_fwd; the call allocates and frees
+ * nothing.  Shapes whose fno_workspace_bytes(FNO_OP_SPECTRAL_CONV_FWD) exceeds the array are
+ * refused with FNO_ENOSPC and nothing is launched.  The first call on a device looks up the
+ * array's address there (make that call outside any capture).  All calls on one GPU share the
+ * array: every byte a call reads from it is written earlier by the same call, so leftovers of the
+ * previous call do no harm, but two calls that overlap in time on one GPU (different streams or
+ * threads) race; order them. */
+#define FNO_STATIC_SCRATCH_BYTES ((size_t)64 << 20)
+int fno_spectral_conv_fwd_static(const fno_desc* desc, const float* x, const float* R, float* y,
+                                 float* xhat_save, void* stream);
+
 /* Per-stage timing for benchmarks.  While enabled, every library call brackets each kernel it
  * launches with a pair of HIP events on the call's stream (events are created on first use and
  * kept).  fno_timing_read waits for the recorded events, returns up to `capacity` records in

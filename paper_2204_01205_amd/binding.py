@@ -20,6 +20,7 @@ FNO_OK, FNO_EINVAL, FNO_EUNSUPPORTED, FNO_ENOSPC, FNO_EHIP = 0, -1, -2, -3, -4
 FNO_ACT_IDENTITY, FNO_ACT_GELU = 0, 1
 FNO_OP_SPECTRAL_CONV_FWD, FNO_OP_SPECTRAL_CONV_BWD, FNO_OP_BLOCK_FWD, FNO_OP_BLOCK_BWD = 0, 1, 2, 3
 FNO_FLAG_MSE_TARGET = 1
+FNO_STATIC_SCRATCH_BYTES = 64 << 20
 
 EXPORTS = [
     "fno_workspace_bytes", "fno_mode_indices", "fno_spectral_conv_fwd", "fno_spectral_conv_bwd",
@@ -27,6 +28,7 @@ EXPORTS = [
     "fno_rel_l2_workspace_bytes", "fno_rel_l2_loss", "fno_adam_step",
     "fno_pointwise_bwd_workspace_bytes", "fno_pointwise_linear_bwd", "fno_pointwise_mlp2_bwd",
     "fno_time_lift_bwd_workspace_bytes", "fno_time_lift_bwd",
+    "fno_spectral_conv_fwd_static",
     "fno_status_string", "fno_timing_enable", "fno_timing_read",
 ]
 
@@ -128,6 +130,12 @@ def fno_spectral_conv_fwd(desc, x, R, y, xhat_save, ws) -> None:
     _check(lib().fno_spectral_conv_fwd(ctypes.byref(desc), _ptr(x, name="x"), _ptr(R, name="R"),
                                        _ptr(y, name="y"), _ptr(xhat_save, name="xhat_save"),
                                        p, n, _stream()))
+
+
+def fno_spectral_conv_fwd_static(desc, x, R, y, xhat_save) -> None:
+    _check(lib().fno_spectral_conv_fwd_static(ctypes.byref(desc), _ptr(x, name="x"), _ptr(R, name="R"),
+                                              _ptr(y, name="y"), _ptr(xhat_save, name="xhat_save"),
+                                              _stream()))
 
 
 def fno_spectral_conv_bwd(desc, x, xhat_saved, R, gy, gx, gR, ws) -> None:

@@ -250,6 +250,11 @@ int conv_bwd_common(const Plan& p, const float* x, const float* xhat_saved, cons
 
 }  // namespace
 
+namespace fno {
+// for the library's other translation units: sets the text fno_status_string returns
+void set_status_detail(const char* text) { set_detail("%s", text); }
+}  // namespace fno
+
 extern "C" {
 
 int fno_workspace_bytes(const fno_desc* desc, int op, size_t* bytes) {
