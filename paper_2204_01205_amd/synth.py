@@ -38,13 +38,18 @@ def retained_counts(modes, rule=0):
     return (f(mx), f(my), f(mz), mt)
 
 
+def normal_slab(seed: int, tensor_id: int, b: int, c: int, grid, std: float = 1.0) -> np.ndarray:
+    """float32 (Nx, Ny, Nz, Nt) ~ N(0, std^2): the (b, c) slab of normal_field(), on its own."""
+    rng = np.random.default_rng([seed, tensor_id, b, c])
+    return (std * rng.standard_normal(tuple(grid))).astype(np.float32)
+
+
 def normal_field(seed: int, tensor_id: int, batch: int, channels: int, grid, std: float = 1.0) -> np.ndarray:
     """float32 (B, C, Nx, Ny, Nz, Nt) ~ N(0, std^2)."""
     out = np.empty((batch, channels) + tuple(grid), np.float32)
     for b in range(batch):
         for c in range(channels):
-            rng = np.random.default_rng([seed, tensor_id, b, c])
-            out[b, c] = (std * rng.standard_normal(tuple(grid))).astype(np.float32)
+            out[b, c] = normal_slab(seed, tensor_id, b, c, grid, std)
     return out
 
 
