@@ -334,6 +334,102 @@ __device__ __forceinline__ void rfft_row_bins(const float4 (&quads)[NT / 4], int
   rfft_bins<NT>(zc, mt, X, std::make_integer_sequence<int, H + 1>{});
 }
 
+// The same bins by a radix-4 split in time, for NT = 16 and 32: with n = 4 m + p,
+//   X[K] = sum_{p<4} w_NT^{pK} D_p[K mod R],   D_p[q] = sum_{m<R} x[4m+p] w_R^{qm},  R = NT / 4,
+// where each D_p is the transform of R real samples (the p-th component of the row's quads): only
+// its bins 0..R/2 are computed, the others are their conjugates, and bins 0 and R/2 are real.
+// About half the arithmetic of the packed complex transform above when few bins are kept.
+// Forward transform of 4 / 8 real samples, bins 0..R/2 (w = exp(-2 pi i / R)).
+__device__ __forceinline__ void real_dft(const float (&a)[4], float2 (&D)[3]) {
+  const float s02 = a[0] + a[2], d02 = a[0] - a[2], s13 = a[1] + a[3], d13 = a[1] - a[3];
+  D[0] = make_float2(s02 + s13, 0.f);
+  D[1] = make_float2(d02, -d13);
+  D[2] = make_float2(s02 - s13, 0.f);
+}
+__device__ __forceinline__ void real_dft(const float (&a)[8], float2 (&D)[5]) {
+  constexpr float r = 0.70710678118654752440f;
+  const float s04 = a[0] + a[4], d04 = a[0] - a[4], s26 = a[2] + a[6], d26 = a[2] - a[6];
+  const float s15 = a[1] + a[5], d15 = a[1] - a[5], s37 = a[3] + a[7], d37 = a[3] - a[7];
+  const float e0 = s04 + s26, e1 = s04 - s26, o0 = s15 + s37, o1 = s15 - s37;
+  const float u = (d15 - d37) * r, v = (d15 + d37) * r;
+  D[0] = make_float2(e0 + o0, 0.f);
+  D[1] = make_float2(d04 + u, -d26 - v);
+  D[2] = make_float2(e1, -o1);
+  D[3] = make_float2(d04 - u, d26 - v);
+  D[4] = make_float2(e0 - o0, 0.f);
+}
+
+// acc += exp(-2 pi i IDX / NT) * v, v complex or (REAL) real-valued
+template <int NT, int IDX, bool REAL>
+__device__ __forceinline__ float2 add_rooted(float2 acc, float2 v) {
+  constexpr int idx = ((IDX % NT) + NT) % NT;
+  constexpr float c = float(ct_cos_frac(idx, NT));
+  constexpr float s = float(-ct_sin_frac(idx, NT));
+  if constexpr (idx == 0) {
+    acc.x += v.x;
+    if constexpr (!REAL) acc.y += v.y;
+  } else if constexpr (2 * idx == NT) {
+    acc.x -= v.x;
+    if constexpr (!REAL) acc.y -= v.y;
+  } else if constexpr (4 * idx == NT) {            // * (-i)
+    if constexpr (!REAL) acc.x += v.y;
+    acc.y -= v.x;
+  } else if constexpr (4 * idx == 3 * NT) {        // * (+i)
+    if constexpr (!REAL) acc.x -= v.y;
+    acc.y += v.x;
+  } else {
+    acc.x = fmaf(c, v.x, acc.x);
+    acc.y = fmaf(s, v.x, acc.y);
+    if constexpr (!REAL) {
+      acc.x = fmaf(-s, v.y, acc.x);
+      acc.y = fmaf(c, v.y, acc.y);
+    }
+  }
+  return acc;
+}
+
+template <int NT, int K>
+__device__ __forceinline__ void rfft4_bin(const float2 (&D)[4][NT / 8 + 1], int mt, float2 (&X)[NT / 2 + 1]) {
+  constexpr int R = NT / 4;
+  constexpr int q = K % R;
+  constexpr bool real_bin = (q == 0) || (2 * q == R);
+  constexpr bool conj_bin = 2 * q > R;
+  constexpr int qi = conj_bin ? R - q : q;
+  if (K < mt) {
+    float2 acc = make_float2(D[0][qi].x, real_bin ? 0.f : (conj_bin ? -D[0][qi].y : D[0][qi].y));
+    acc = add_rooted<NT, 1 * K, real_bin>(acc, make_float2(D[1][qi].x, conj_bin ? -D[1][qi].y : D[1][qi].y));
+    acc = add_rooted<NT, 2 * K, real_bin>(acc, make_float2(D[2][qi].x, conj_bin ? -D[2][qi].y : D[2][qi].y));
+    acc = add_rooted<NT, 3 * K, real_bin>(acc, make_float2(D[3][qi].x, conj_bin ? -D[3][qi].y : D[3][qi].y));
+    X[K] = acc;
+  }
+}
+
+template <int NT, int... Ks>
+__device__ __forceinline__ void rfft4_bins(const float2 (&D)[4][NT / 8 + 1], int mt, float2 (&X)[NT / 2 + 1],
+                                           std::integer_sequence<int, Ks...>) {
+  (rfft4_bin<NT, Ks>(D, mt, X), ...);
+}
+
+template <int NT>
+__device__ __forceinline__ void rfft_row_bins_r4(const float4 (&quads)[NT / 4], int mt, float2 (&X)[NT / 2 + 1]) {
+  constexpr int R = NT / 4;
+  float2 D[4][R / 2 + 1];
+  float a[R];
+#pragma unroll
+  for (int m = 0; m < R; ++m) a[m] = quads[m].x;
+  real_dft(a, D[0]);
+#pragma unroll
+  for (int m = 0; m < R; ++m) a[m] = quads[m].y;
+  real_dft(a, D[1]);
+#pragma unroll
+  for (int m = 0; m < R; ++m) a[m] = quads[m].z;
+  real_dft(a, D[2]);
+#pragma unroll
+  for (int m = 0; m < R; ++m) a[m] = quads[m].w;
+  real_dft(a, D[3]);
+  rfft4_bins<NT>(D, mt, X, std::make_integer_sequence<int, NT / 2 + 1>{});
+}
+
 // One thread per z-row (blockDim.x >= ppb * Nz).  The planes and the z twiddles go straight to
 // LDS (16 bytes per lane, 1 KiB per wave instruction, nothing staged in registers).  Inside a
 // row the quads are stored rotated by the row number so that the row-per-thread reads of the
@@ -390,7 +486,8 @@ __global__ __launch_bounds__(kThreads) void tz_fwd_fast_kernel(
 #pragma unroll
     for (int q = 0; q < QPR; ++q)
       quads[q] = *reinterpret_cast<const float4*>(S + 4 * (tid * QPR + ((q + tid / ROT) & (QPR - 1))));
-    rfft_row_bins<NT>(quads, mt, X);
+    if constexpr (NT == 16 || NT == 32) rfft_row_bins_r4<NT>(quads, mt, X);
+    else rfft_row_bins<NT>(quads, mt, X);
   }
   __syncthreads();
   if (live) {
@@ -693,7 +790,9 @@ hipError_t launch_tz_fwd(const float* x, float2* out, const float2* twt, const f
                     tz_fast_lds(az, Nt, mt, 1) <= (size_t)kLdsBudget;
   if (fast) {
     int ppb = 1;
-    while (ppb * 2 * az.N <= 256 && tz_fast_lds(az, Nt, mt, ppb * 2) <= (size_t)kLdsBudget) ppb *= 2;
+    // one plane of 128 rows per block: the smaller LDS share keeps more blocks resident, which hides
+    // the compute phases behind other blocks' loads a little better than two planes per block
+    while (ppb * 2 * az.N <= 128 && tz_fast_lds(az, Nt, mt, ppb * 2) <= (size_t)kLdsBudget) ppb *= 2;
     const int thr = ((ppb * az.N + 63) / 64) * 64;
     const size_t lds = tz_fast_lds(az, Nt, mt, ppb);
     const int region = tz_fast_region(az, Nt, mt, ppb);

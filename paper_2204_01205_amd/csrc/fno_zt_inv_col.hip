@@ -1,6 +1,7 @@
 // Inverse (z, t) + block epilogue, column variant on the matrix cores (see fno_zt_inv.hip for
 // what the stage computes and fno_zt_inv_mfma.hip for the lane layout of the 4x4x1 MFMA blocks).
 #include "fno_zt_inv.h"
+#include <type_traits>
 
 namespace fno {
 
@@ -13,12 +14,21 @@ namespace {
 // (z stage, t stage, W part, epilogue), one per slot of u registers.  Slot s of lane block (wave, blk) is the quad
 // blk % 8 of row z = Pz (2 wave + blk / 8) + 2 step + s.  Launch: grid (NxNy, B), 512 threads.
 // The table blob is the one of zt_tables_kernel with Q = Pz (all twiddles, [Pz][Lz]).
-template <int CT, bool FULL>
+// MTC, LZC: the kept counts on t and z as compile-time constants (0: taken from the arguments), so
+// that the loops over them unroll; EPI >= 0 fixes the epilogue at compile time (bit 0: GELU, bit 1:
+// the pre-activation is stored as well), EPI = -1 reads it from the arguments.  With a fixed
+// epilogue every half step issues the same number of loads and stores on every path, which the
+// compiler's wait counts for the prefetched u values rely on.
+template <int CT, bool FULL, int MTC, int LZC, int EPI>
 __global__ __launch_bounds__(512, 4) void zt_inv_col_kernel(
-    const float2* __restrict__ a, float* __restrict__ out, int Co_rt, int NxNy, int Nz, int Lz,
-    int nposz, int mt, int inv_mt, int a_floats, int a_stride4, int v_stride,
+    const float2* __restrict__ a, float* __restrict__ out, int Co_rt, int NxNy, int Nz, int Lz_rt,
+    int nposz, int mt_rt, int inv_mt, int a_floats, int a_stride4, int v_stride,
     const float* __restrict__ blob, int blob_floats, EpiArgs ep) {
   HIP_DYNAMIC_SHARED(float, smem)
+  const int mt = MTC ? MTC : mt_rt;
+  const int Lz = LZC ? LZC : Lz_rt;
+  const bool act = EPI >= 0 ? (EPI & 1) != 0 : ep.act != 0;
+  const bool zsave = EPI >= 0 ? (EPI & 2) != 0 : ep.zsave != nullptr;
   constexpr int NT = 32, MZ = 16, NW = 8;
   constexpr int CP = 4 * CT;
   constexpr int CI = CP;
@@ -30,7 +40,7 @@ __global__ __launch_bounds__(512, 4) void zt_inv_col_kernel(
   float2* V = reinterpret_cast<float2*>(smem + a_floats);       // [CP][MZ][mt], padded channel stride
   float* CS = smem + a_floats + 2 * CP * v_stride;              // [2 mt][NT]: cos rows and -sin rows
   float* Wt = CS + 2 * mt * NT;                                 // [Cu][CP]
-  const bool lin = ep.u != nullptr;
+  const bool lin = EPI >= 0 ? true : ep.u != nullptr;      // a fixed epilogue always has the linear term
   const float2* TW = reinterpret_cast<const float2*>(Wt + (lin ? Cu * CP : 0));   // [Pz][Lz]
   const int tid = threadIdx.x;
   const int xy = blockIdx.x;
@@ -96,9 +106,19 @@ __global__ __launch_bounds__(512, 4) void zt_inv_col_kernel(
     __builtin_amdgcn_s_waitcnt(0x0F70);
   }
   __syncthreads();
+  // The bias rides on the spectrum: adding b[o] to the entry (kz = 0, kt = 0) of channel o (stored
+  // first: j = 0, kt = 0) adds b[o] to every point of the channel (that entry's z twiddle and its
+  // cos row are 1), so the accumulators below start from zero.
+  if (tid < Co) smem[tid * (4 * a_stride4)] += BI[tid];
+  __syncthreads();
 
   const int nsteps = Pz >> 1;
-  for (int step = 0; step < nsteps; ++step) {
+  // One step = two half steps.  PREFETCH: the step also loads the u values of the next step.  The
+  // last step of a column has no next step; it runs as a copy of the body without those loads, so
+  // that inside the loop every half step issues the same number of loads on every path and the
+  // compiler can count how many later memory operations may still be in flight when a u value is used.
+  auto run_step = [&](const int step, auto prefetch_tag) {
+    constexpr bool PREFETCH = decltype(prefetch_tag)::value;
 #pragma unroll
     for (int sl = 0; sl < 2; ++sl) {
       const int n2 = 2 * step + sl;                       // residue class of this half step
@@ -112,9 +132,10 @@ __global__ __launch_bounds__(512, 4) void zt_inv_col_kernel(
         // together.  Other Lz take one term at a time.
         const float2* twq = TW + n2 * Lz;
         float2 gres[MZ];
-#pragma unroll
-        for (int m = 0; m < MZ; ++m) gres[m] = make_float2(0.f, 0.f);
         if ((Lz & (MZ - 1)) == 0) {
+#pragma unroll
+          for (int m = 0; m < MZ; ++m) gres[m] = make_float2(0.f, 0.f);
+#pragma unroll
           for (int r0 = 0; r0 < Lz; r0 += MZ) {
             const float2* ar = asrc + r0 * mt;
             const float2* tr = twq + r0;
@@ -132,6 +153,8 @@ __global__ __launch_bounds__(512, 4) void zt_inv_col_kernel(
           }
         } else {
 #pragma unroll
+          for (int m = 0; m < MZ; ++m) gres[m] = make_float2(0.f, 0.f);
+#pragma unroll
           for (int m = 0; m < MZ; ++m) {
             for (int k = kmin + ((m + mbase) & (MZ - 1)); k <= kmax; k += MZ) {
               const int j = k >= 0 ? k : k + Lz;
@@ -147,14 +170,12 @@ __global__ __launch_bounds__(512, 4) void zt_inv_col_kernel(
       // t stage: complex-to-real step over kt on the matrix cores
       v4f acc[CT];
 #pragma unroll
-      for (int T = 0; T < CT; ++T) {
-        const float bv = BI[4 * T + j4];
-        acc[T] = v4f{bv, bv, bv, bv};
-      }
+      for (int T = 0; T < CT; ++T) acc[T] = v4f{0.f, 0.f, 0.f, 0.f};
       const float* cs_lane = CS + 4 * quad + j4;
       const float2* v0 = V + j4 * v_stride + n1 * mt;
       int kt = 0;
       constexpr int KB = 3;                       // kt per pass: their reads go out together
+#pragma unroll 1
       for (; kt + KB <= mt; kt += KB) {
         float cs4[2 * KB];
         float2 va[KB][CT];
@@ -173,6 +194,7 @@ __global__ __launch_bounds__(512, 4) void zt_inv_col_kernel(
             acc[T] = __builtin_amdgcn_mfma_f32_4x4x1f32(cs4[2 * h + 1], va[h][T].y, acc[T], 0, 0, 0);
           }
       }
+#pragma unroll
       for (; kt < mt; ++kt) {
         const float c = cs_lane[(2 * kt) * NT];
         const float sn = cs_lane[(2 * kt + 1) * NT];
@@ -207,7 +229,7 @@ __global__ __launch_bounds__(512, 4) void zt_inv_col_kernel(
         }
         // this slot's u values of the next step
         asm volatile("" ::: "memory");
-        if (step + 1 < nsteps) {
+        if constexpr (PREFETCH) {
 #pragma unroll
           for (int i = 0; i < CI; ++i)
             if (FULL || i < Cu) xv[i][sl] = ubase[i * Npts + (n2 + 2) * NT];
@@ -216,14 +238,14 @@ __global__ __launch_bounds__(512, 4) void zt_inv_col_kernel(
       }
       // lane 4b+j now holds channel 4T+j at the four t of its quad
       float* op = out + (b * Co + j4) * Npts + poff;
-      if (ep.zsave != nullptr) {
+      if (zsave) {
         float* zp = ep.zsave + (b * Co + j4) * Npts + poff;
 #pragma unroll
         for (int T = 0; T < CT; ++T)
           if (FULL || 4 * T + j4 < Co)
             *reinterpret_cast<float4*>(zp + (4 * T) * Npts) = make_float4(acc[T][0], acc[T][1], acc[T][2], acc[T][3]);
       }
-      if (ep.act) {
+      if (act) {
 #pragma unroll
         for (int T = 0; T < CT; ++T)
           if (FULL || 4 * T + j4 < Co)
@@ -237,7 +259,9 @@ __global__ __launch_bounds__(512, 4) void zt_inv_col_kernel(
             *reinterpret_cast<float4*>(op + (4 * T) * Npts) = make_float4(acc[T][0], acc[T][1], acc[T][2], acc[T][3]);
       }
     }
-  }
+  };
+  for (int step = 0; step + 1 < nsteps; ++step) run_step(step, std::true_type{});
+  run_step(nsteps - 1, std::false_type{});
 }
 
 }  // namespace
@@ -265,12 +289,19 @@ hipError_t launch_zt_inv_col(const float2* a, float* out, const float2* twt, con
                                          Cu, 4 * CT, mt, Nt, Nt, az.L, az.P, az.P, blob_floats, s);
       if (terr != hipSuccess) return terr;
       const dim3 grid((unsigned)NxNy, (unsigned)B);
-#define FNO_ZTC(CTV, FULLV)                                                                        \
-  hipLaunchKernelGGL((zt_inv_col_kernel<CTV, FULLV>), grid, dim3(512), lds, s, a, out, Co, NxNy,   \
-                     az.N, az.L, az.npos, mt, inv_mt, a_floats, a_stride4, v_stride, tables,       \
+#define FNO_ZTC(CTV, FULLV, MTV, LZV, EPIV)                                                            \
+  hipLaunchKernelGGL((zt_inv_col_kernel<CTV, FULLV, MTV, LZV, EPIV>), grid, dim3(512), lds, s, a, out, Co, \
+                     NxNy, az.N, az.L, az.npos, mt, inv_mt, a_floats, a_stride4, v_stride, tables,         \
                      blob_floats, e)
-      if (CT == 2) { if (full) FNO_ZTC(2, true); else FNO_ZTC(2, false); }
-      else { if (full) FNO_ZTC(5, true); else FNO_ZTC(5, false); }
+      // the shape of the large workloads (width 20, 9 kept t bins, 32 kept z frequencies) with its three
+      // epilogues: forward, forward that keeps the pre-activation, and the adjoint's linear one
+      const int epi = (e.act ? 1 : 0) | (e.zsave != nullptr ? 2 : 0);
+      if (CT == 5 && full && mt == 9 && az.L == 32 && e.u != nullptr && epi != 2) {
+        if (epi == 1) FNO_ZTC(5, true, 9, 32, 1);
+        else if (epi == 3) FNO_ZTC(5, true, 9, 32, 3);
+        else FNO_ZTC(5, true, 9, 32, 0);
+      } else if (CT == 2) { if (full) FNO_ZTC(2, true, 0, 0, -1); else FNO_ZTC(2, false, 0, 0, -1); }
+      else { if (full) FNO_ZTC(5, true, 0, 0, -1); else FNO_ZTC(5, false, 0, 0, -1); }
 #undef FNO_ZTC
       *taken = true;
       return hipGetLastError();
