@@ -21,7 +21,7 @@ __device__ __forceinline__ float gelu_f(float z) {
 //   erf(x) = 1 - (1 + a1 x + ... + a6 x^6)^-16          (Abramowitz & Stegun 7.1.28, |error| <= 3e-7)
 // the upper tail is T(a) = (1 - erf(a / sqrt 2)) / 2 = q(a)^-16 with q(a) = 2^(1/16) (1 + sum_i a_i (a / sqrt 2)^i),
 // and z Phi(z) = max(z, 0) - a T(a).  The constants below are q's coefficients 2^(1/16) a_i 2^(-i/2).
-// 17 issue slots per value (the reciprocal counts four).  Error against the float64 definition,
+// 16 issue slots per value (the reciprocal counts four).  Error against the float64 definition,
 // evaluated in float32: at most 7.1e-7 absolute.
 __device__ __forceinline__ float gelu_fast_f(float z) {
   const float a = fabsf(z);
@@ -33,7 +33,8 @@ __device__ __forceinline__ float gelu_fast_f(float z) {
   q = fmaf(a, q, 1.0442737824f);
   q = q * q; q = q * q; q = q * q; q = q * q;
   const float t = __builtin_amdgcn_rcpf(q);             // v_rcp_f32, 1 ulp
-  return fmaf(-a, t, fmaxf(z, 0.0f));
+  // max(z, 0) as a median of three (one instruction; fmaxf would first quiet a signalling NaN)
+  return fmaf(-a, t, __builtin_amdgcn_fmed3f(z, 0.0f, __builtin_inff()));
 }
 __device__ __forceinline__ float gelu_prime_f(float z) {
   const float cdf = 0.5f * (1.0f + erff(z * 0.70710678118654752440f));

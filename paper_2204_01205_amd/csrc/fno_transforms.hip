@@ -512,19 +512,36 @@ __global__ __launch_bounds__(kThreads) void tz_fwd_fast_kernel(
     __syncthreads();
   }
 
-  for (int p = 0; p < np; ++p) {
-    float2* dst = out + (plane0 + p) * (long long)(Lz * mt);
-    for (int idx = tid; idx < Lz * mt; idx += nthr) {
-      const int jz = (idx * inv_mt) >> 16;
-      const int kt = idx - jz * mt;
+  // twiddle combine at the kept z-frequencies, all planes of the block in one index range; for the
+  // usual residue-class counts the terms of a sum are read together, then multiplied
+  const int per = Lz * mt, total = np * per;
+  const unsigned inv_per = 0xFFFFFFFFu / (unsigned)per + 1u;      // idx / per == umulhi(idx, inv_per) for idx < 2^16
+  auto combine = [&](auto pz_tag) {
+    constexpr int PZ = decltype(pz_tag)::value;                   // 0: taken from the argument
+    for (int idx = tid; idx < total; idx += nthr) {
+      const int p = (int)__umulhi((unsigned)idx, inv_per);
+      const int r = idx - p * per;
+      const int jz = (r * inv_mt) >> 16;
+      const int kt = r - jz * mt;
       const int mj = posmod(kfreq(jz, Lz, nposz), MZ);
       const float2* base = T + (p * mt + kt) * sT + (mj << pzshift);
       const float2* w = TW + (jz << pzshift);
       float2 acc = make_float2(0.f, 0.f);
-      for (int n2 = 0; n2 < Pz; ++n2) acc = cfma(w[n2], base[n2], acc);
-      dst[idx] = acc;
+      if constexpr (PZ > 0) {
+        float2 wv[PZ], bv[PZ];
+#pragma unroll
+        for (int n2 = 0; n2 < PZ; ++n2) { wv[n2] = w[n2]; bv[n2] = base[n2]; }
+#pragma unroll
+        for (int n2 = 0; n2 < PZ; ++n2) acc = cfma(wv[n2], bv[n2], acc);
+      } else {
+        for (int n2 = 0; n2 < Pz; ++n2) acc = cfma(w[n2], base[n2], acc);
+      }
+      out[(plane0 + p) * (long long)per + r] = acc;
     }
-  }
+  };
+  if (pzshift == 3) combine(std::integral_constant<int, 8>{});
+  else if (pzshift == 2) combine(std::integral_constant<int, 4>{});
+  else combine(std::integral_constant<int, 0>{});
 }
 
 // ------------------------------------------------------------------------------------------
@@ -634,41 +651,42 @@ __device__ __forceinline__ float mode_scale(long long k, int mt, int Nt, float i
   return single ? invN : 2.0f * invN;
 }
 
-constexpr int kMixB = 4;   // batch entries held per pass
-constexpr int kMixO = 4;   // output channels per thread in the forward mix
+constexpr int kMixB = 4;   // batch entries held per pass (backward mix)
 
+// One thread: one mode, KO output channels, KB batch entries per pass; R is read exactly once,
+// the input spectrum once per group of KO output channels (launch: grid.y = ceil(Co / KO)).
+template <int KB, int KO>
 __global__ __launch_bounds__(kThreads) void mix_fwd_kernel(
     const float2* __restrict__ xh, const float2* __restrict__ R, float2* __restrict__ yh, int B,
     int Ci, int Co, long long K, int mt, int Nt, float invN) {
-  // one thread: one mode, kMixO output channels, kMixB batch entries; R is read exactly once
   const long long k = (long long)blockIdx.x * kThreads + threadIdx.x;
-  const int o0 = blockIdx.y * kMixO;
+  const int o0 = blockIdx.y * KO;
   if (k >= K) return;
   const float sc = mode_scale(k, mt, Nt, invN);
-  for (int b0 = 0; b0 < B; b0 += kMixB) {
-    float2 acc[kMixB][kMixO];
+  for (int b0 = 0; b0 < B; b0 += KB) {
+    float2 acc[KB][KO];
 #pragma unroll
-    for (int u = 0; u < kMixB; ++u)
+    for (int u = 0; u < KB; ++u)
 #pragma unroll
-      for (int v = 0; v < kMixO; ++v) acc[u][v] = make_float2(0.f, 0.f);
+      for (int v = 0; v < KO; ++v) acc[u][v] = make_float2(0.f, 0.f);
     for (int i = 0; i < Ci; ++i) {
-      float2 xv[kMixB];
+      float2 xv[KB];
 #pragma unroll
-      for (int u = 0; u < kMixB; ++u)
+      for (int u = 0; u < KB; ++u)
         xv[u] = (b0 + u < B) ? xh[((long long)(b0 + u) * Ci + i) * K + k] : make_float2(0.f, 0.f);
 #pragma unroll
-      for (int v = 0; v < kMixO; ++v) {
+      for (int v = 0; v < KO; ++v) {
         if (o0 + v < Co) {
           const float2 r = R[((long long)i * Co + o0 + v) * K + k];
 #pragma unroll
-          for (int u = 0; u < kMixB; ++u) acc[u][v] = cfma(xv[u], r, acc[u][v]);
+          for (int u = 0; u < KB; ++u) acc[u][v] = cfma(xv[u], r, acc[u][v]);
         }
       }
     }
 #pragma unroll
-    for (int u = 0; u < kMixB; ++u)
+    for (int u = 0; u < KB; ++u)
 #pragma unroll
-      for (int v = 0; v < kMixO; ++v)
+      for (int v = 0; v < KO; ++v)
         if (b0 + u < B && o0 + v < Co)
           yh[((long long)(b0 + u) * Co + o0 + v) * K + k] = make_float2(acc[u][v].x * sc, acc[u][v].y * sc);
   }
@@ -875,7 +893,9 @@ hipError_t launch_mix_fwd(const float2* xh, const float2* R, float2* yh, int B, 
                           int64_t K, int mt, int Nt, double invN, hipStream_t s) {
   const int64_t nb = (K + kThreads - 1) / kThreads;
   if (nb > 0x7fffffffLL || Co > 65535) return hipErrorInvalidValue;
-  hipLaunchKernelGGL(mix_fwd_kernel, dim3((unsigned)nb, (unsigned)((Co + kMixO - 1) / kMixO)), dim3(kThreads), 0, s, xh, R,
+  // four output channels and four batch entries per thread; wider output tiles (10 or 20 channels
+  // for a single batch entry, which would read the input spectrum less often) measured slower
+  hipLaunchKernelGGL((mix_fwd_kernel<4, 4>), dim3((unsigned)nb, (unsigned)((Co + 3) / 4)), dim3(kThreads), 0, s, xh, R,
                      yh, B, Ci, Co, (long long)K, mt, Nt, (float)invN);
   return hipGetLastError();
 }
