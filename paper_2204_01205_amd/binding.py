@@ -20,6 +20,7 @@ FNO_OK, FNO_EINVAL, FNO_EUNSUPPORTED, FNO_ENOSPC, FNO_EHIP = 0, -1, -2, -3, -4
 FNO_ACT_IDENTITY, FNO_ACT_GELU = 0, 1
 FNO_OP_SPECTRAL_CONV_FWD, FNO_OP_SPECTRAL_CONV_BWD, FNO_OP_BLOCK_FWD, FNO_OP_BLOCK_BWD = 0, 1, 2, 3
 FNO_FLAG_MSE_TARGET = 1
+FNO_FLAG_ACCUMULATE_GRADS = 2
 FNO_STATIC_SCRATCH_BYTES = 64 << 20
 
 EXPORTS = [
@@ -92,6 +93,44 @@ def _ptr(t: Optional[torch.Tensor], dtype=torch.float32, name: str = "tensor"):
     return ctypes.c_void_p(t.data_ptr())
 
 
+def _sizes(desc: FnoDesc):
+    """(grid points, kept modes) per (batch, channel) slab, from the library's own mode lists."""
+    npts = 1
+    for n in desc.grid:
+        npts *= int(n)
+    kept = 1
+    for axis in range(4):
+        n = ctypes.c_int32(0)
+        _check(lib().fno_mode_indices(ctypes.byref(desc), ctypes.c_int(axis), None, ctypes.byref(n)))
+        kept *= int(n.value)
+    return npts, kept
+
+
+def _expect(t: Optional[torch.Tensor], name: str, numel: int) -> None:
+    """A tensor handed to the kernels must hold exactly the elements the descriptor implies: the
+    kernels index by the descriptor alone, and a short buffer would be read or written out of bounds."""
+    if t is None:
+        return
+    have = t.numel() * (2 if t.dtype == torch.complex64 else 1)
+    if have != numel:
+        raise ValueError(f"{name} holds {have} floats, the descriptor implies {numel}")
+
+
+def _check_layer_tensors(desc, *, x=None, y=None, R=None, xhat=None, W=None, b=None, extra_in=(), extra_out=()):
+    npts, kept = _sizes(desc)
+    B_, ci, co = int(desc.batch), int(desc.c_in), int(desc.c_out)
+    _expect(x, "x", B_ * ci * npts)
+    _expect(y, "output", B_ * co * npts)
+    _expect(R, "R", 2 * ci * co * kept)
+    _expect(xhat, "xhat", 2 * B_ * ci * kept)
+    _expect(W, "W", co * ci)
+    _expect(b, "b", co)
+    for name, t in extra_in:
+        _expect(t, name, B_ * ci * npts)
+    for name, t in extra_out:
+        _expect(t, name, B_ * co * npts)
+
+
 def _stream():
     return ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
 
@@ -126,6 +165,7 @@ def _ws(ws: torch.Tensor):
 
 
 def fno_spectral_conv_fwd(desc, x, R, y, xhat_save, ws) -> None:
+    _check_layer_tensors(desc, x=x, y=y, R=R, xhat=xhat_save)
     p, n = _ws(ws)
     _check(lib().fno_spectral_conv_fwd(ctypes.byref(desc), _ptr(x, name="x"), _ptr(R, name="R"),
                                        _ptr(y, name="y"), _ptr(xhat_save, name="xhat_save"),
@@ -133,12 +173,15 @@ def fno_spectral_conv_fwd(desc, x, R, y, xhat_save, ws) -> None:
 
 
 def fno_spectral_conv_fwd_static(desc, x, R, y, xhat_save) -> None:
+    _check_layer_tensors(desc, x=x, y=y, R=R, xhat=xhat_save)
     _check(lib().fno_spectral_conv_fwd_static(ctypes.byref(desc), _ptr(x, name="x"), _ptr(R, name="R"),
                                               _ptr(y, name="y"), _ptr(xhat_save, name="xhat_save"),
                                               _stream()))
 
 
 def fno_spectral_conv_bwd(desc, x, xhat_saved, R, gy, gx, gR, ws) -> None:
+    _check_layer_tensors(desc, x=x, y=gy, R=R, xhat=xhat_saved, extra_in=(("gx", gx),))
+    _expect(gR, "gR", R.numel() * 2 if R is not None else 0)
     p, n = _ws(ws)
     _check(lib().fno_spectral_conv_bwd(ctypes.byref(desc), _ptr(x, name="x"),
                                        _ptr(xhat_saved, name="xhat_saved"), _ptr(R, name="R"),
@@ -147,6 +190,7 @@ def fno_spectral_conv_bwd(desc, x, xhat_saved, R, gy, gx, gR, ws) -> None:
 
 
 def fno_block_fwd(desc, x, R, W, b, out, z_save, xhat_save, ws) -> None:
+    _check_layer_tensors(desc, x=x, y=out, R=R, xhat=xhat_save, W=W, b=b, extra_out=(("z_save", z_save),))
     p, n = _ws(ws)
     _check(lib().fno_block_fwd(ctypes.byref(desc), _ptr(x, name="x"), _ptr(R, name="R"),
                                _ptr(W, name="W"), _ptr(b, name="b"), _ptr(out, name="out"),
@@ -155,6 +199,10 @@ def fno_block_fwd(desc, x, R, W, b, out, z_save, xhat_save, ws) -> None:
 
 
 def fno_block_bwd(desc, x, R, W, z_saved, xhat_saved, gout, gx, gR, gW, gb, ws) -> None:
+    _check_layer_tensors(desc, x=x, y=gout, R=R, xhat=xhat_saved, W=W, b=gb,
+                         extra_in=(("gx", gx),), extra_out=(("z_saved", z_saved),))
+    _expect(gR, "gR", R.numel() * 2 if R is not None else 0)
+    _expect(gW, "gW", W.numel() if W is not None else 0)
     p, n = _ws(ws)
     _check(lib().fno_block_bwd(ctypes.byref(desc), _ptr(x, name="x"), _ptr(R, name="R"),
                                _ptr(W, name="W"), _ptr(z_saved, name="z_saved"),

@@ -47,7 +47,7 @@ int make_plan(const fno_desc* d, bool need_block, bool need_bwd_block, Plan* p) 
   if (d->batch < 1 || d->c_in < 1 || d->c_out < 1) { set_detail("batch and channel widths must be >= 1"); return FNO_EINVAL; }
   if (d->mode_rule != 0 && d->mode_rule != 1) { set_detail("mode_rule must be 0 or 1"); return FNO_EINVAL; }
   if (d->activation != FNO_ACT_IDENTITY && d->activation != FNO_ACT_GELU) { set_detail("unknown activation"); return FNO_EINVAL; }
-  if (d->flags & ~FNO_FLAG_MSE_TARGET) { set_detail("unknown flag bits"); return FNO_EINVAL; }
+  if (d->flags & ~(FNO_FLAG_MSE_TARGET | FNO_FLAG_ACCUMULATE_GRADS)) { set_detail("unknown flag bits"); return FNO_EINVAL; }
   for (int a = 0; a < 4; ++a) {
     if (d->grid[a] < 1) { set_detail("grid sizes must be >= 1"); return FNO_EINVAL; }
     if (d->modes[a] < (a == 3 ? 1 : 0)) { set_detail("mode counts must be non-negative (mt >= 1)"); return FNO_EINVAL; }
@@ -227,7 +227,8 @@ int conv_fwd_common(const Plan& p, const float* x, const float* R, float* out, f
 
 // shared by the two backward calls; gz is dL/d(pre-activation) [B][Co][grid]
 int conv_bwd_common(const Plan& p, const float* x, const float* xhat_saved, const float* R,
-                    const float* gz, float* gx, float* gR, void* ws, fno::Epilogue ep, hipStream_t s) {
+                    const float* gz, float* gx, float* gR, void* ws, fno::Epilogue ep, int accumulate,
+                    hipStream_t s) {
   int rc;
   const float2* xh = reinterpret_cast<const float2*>(xhat_saved);
   if (gR != nullptr && xh == nullptr) {
@@ -243,7 +244,7 @@ int conv_bwd_common(const Plan& p, const float* x, const float* xhat_saved, cons
   float2* gxh = gx != nullptr ? at<float2>(ws, p.off_s2) : nullptr;
   FNO_STAGE(FNO_STAGE_MIX_BWD, s, fno::launch_mix_bwd(xh, reinterpret_cast<const float2*>(R), gh,
                               reinterpret_cast<float2*>(gR), gxh, p.B, p.Ci, p.Co, p.K, p.mt, p.Nt,
-                              1.0 / double(p.Npts), s));
+                              1.0 / double(p.Npts), accumulate, s));
   if (gx != nullptr) return inverse_chain(p, ws, gxh, p.Ci, gx, ep, s);
   return FNO_OK;
 }
@@ -310,7 +311,7 @@ int fno_spectral_conv_bwd(const fno_desc* desc, const float* x, const float* xha
   rc = build_tables(p, ws, s);
   if (rc != FNO_OK) return rc;
   fno::Epilogue ep{nullptr, 0, nullptr, 0, 0, nullptr, nullptr, 0};
-  return conv_bwd_common(p, x, xhat_saved, R, gy, gx, gR, ws, ep, s);
+  return conv_bwd_common(p, x, xhat_saved, R, gy, gx, gR, ws, ep, (desc->flags & FNO_FLAG_ACCUMULATE_GRADS) ? 1 : 0, s);
 }
 
 int fno_block_fwd(const fno_desc* desc, const float* x, const float* R, const float* W,
@@ -346,16 +347,17 @@ int fno_block_bwd(const fno_desc* desc, const float* x, const float* R, const fl
   float* gz = at<float>(ws, p.off_gz);
   double* part = at<double>(ws, p.off_part);
   const int mse = (desc->flags & FNO_FLAG_MSE_TARGET) ? 1 : 0;
+  const int accumulate = (desc->flags & FNO_FLAG_ACCUMULATE_GRADS) ? 1 : 0;
   const double mse_scale = 2.0 / (double(p.B) * double(p.Co) * double(p.Npts));
   int nslots = 0;
   FNO_STAGE(FNO_STAGE_BWD_POINTWISE, s, fno::launch_bwd_pointwise(z_saved, gout, x, gz, part, &nslots, p.B, p.Ci, p.Co,
                                     p.Npts, desc->activation, mse, mse_scale, s));
   if (gW != nullptr || gb != nullptr)
-    FNO_HIP(fno::launch_reduce_partials(part, nslots, p.Co, p.Ci, gW, gb, s));
+    FNO_HIP(fno::launch_reduce_partials(part, nslots, p.Co, p.Ci, gW, gb, accumulate, s));
   if (gx == nullptr && gR == nullptr) return FNO_OK;
   // gx = K(R^H) gz + W^T gz : the epilogue applies W transposed to gz, no bias, no activation
   fno::Epilogue ep{gz, p.Co, W, 1, p.Ci, nullptr, nullptr, 0};
-  return conv_bwd_common(p, x, xhat_saved, R, gz, gx, gR, ws, ep, s);
+  return conv_bwd_common(p, x, xhat_saved, R, gz, gx, gR, ws, ep, accumulate, s);
 }
 
 int fno_pointwise_linear(int32_t batch, int32_t c_in, int32_t c_out, int64_t npoints, const float* x,

@@ -34,10 +34,10 @@ hipError_t launch_axis_inv(const float2* in, float2* out, const float2* tw, int6
 hipError_t launch_mix_fwd(const float2* xh, const float2* R, float2* yh, int B, int Ci, int Co,
                           int64_t K, int mt, int Nt, double invN, hipStream_t s);
 // gR[i][o][k] = sum_b conj(xh[b][i][k]) gy[b][o][k],  gxh[b][i][k] = sum_o conj(R[i][o][k]) gy[b][o][k]
-// with gy = (c_kt / N) gh.  gR and gxh nullable.
+// with gy = (c_kt / N) gh.  gR and gxh nullable; accumulate: the sum over b is added to what gR holds.
 hipError_t launch_mix_bwd(const float2* xh, const float2* R, const float2* gh, float2* gR,
                           float2* gxh, int B, int Ci, int Co, int64_t K, int mt, int Nt,
-                          double invN, hipStream_t s);
+                          double invN, int accumulate, hipStream_t s);
 
 struct Epilogue {
   const float* u;      // [B][Cu][grid] tensor the channel-linear term acts on, or nullptr
@@ -62,7 +62,7 @@ hipError_t launch_bwd_pointwise(const float* z, const float* gout, const float* 
                                 double* part, int* nslots, int B, int Ci, int Co, int64_t N, int act,
                                 int mse_target, double mse_scale, hipStream_t s);
 hipError_t launch_reduce_partials(const double* part, int nblk, int Co, int Ci, float* gW,
-                                  float* gb, hipStream_t s);
+                                  float* gb, int accumulate, hipStream_t s);
 int bwd_pointwise_blocks(int B, int64_t N);
 
 hipError_t launch_pointwise_linear(int B, int Ci, int Co, int64_t np, const float* x, const float* W,

@@ -212,7 +212,7 @@ __global__ __launch_bounds__(kThreads) void bwd_pointwise_mfma_kernel(
 constexpr int kRedGroups = 16;
 __global__ __launch_bounds__(64 * kRedGroups) void reduce_partials_kernel(
     const double* __restrict__ part, int nblk, int Co, int Ci, float* __restrict__ gW,
-    float* __restrict__ gb) {
+    float* __restrict__ gb, int accumulate) {
   __shared__ double sums[kRedGroups][64];
   const int lane = threadIdx.x & 63, grp = threadIdx.x >> 6;
   const int q = blockIdx.x * 64 + lane;
@@ -236,8 +236,9 @@ __global__ __launch_bounds__(64 * kRedGroups) void reduce_partials_kernel(
     double t = 0.0;
 #pragma unroll
     for (int g = 0; g < kRedGroups; ++g) t += sums[g][lane];
-    if (q < Co * Ci) { if (gW != nullptr) gW[q] = float(t); }
-    else if (gb != nullptr) gb[q - Co * Ci] = float(t);
+    // accumulate: the sums are added to what gW and gb hold (a step over several calls)
+    if (q < Co * Ci) { if (gW != nullptr) gW[q] = float(accumulate ? t + double(gW[q]) : t); }
+    else if (gb != nullptr) gb[q - Co * Ci] = float(accumulate ? t + double(gb[q - Co * Ci]) : t);
   }
 }
 
@@ -985,10 +986,10 @@ hipError_t launch_bwd_pointwise(const float* z, const float* gout, const float* 
 }
 
 hipError_t launch_reduce_partials(const double* part, int nblk, int Co, int Ci, float* gW,
-                                  float* gb, hipStream_t s) {
+                                  float* gb, int accumulate, hipStream_t s) {
   const int npairs = Co * Ci + Co;
   hipLaunchKernelGGL(reduce_partials_kernel, dim3((npairs + 63) / 64), dim3(64 * kRedGroups), 0, s, part,
-                     nblk, Co, Ci, gW, gb);
+                     nblk, Co, Ci, gW, gb, accumulate);
   return hipGetLastError();
 }
 
@@ -1155,7 +1156,7 @@ hipError_t launch_pointwise_linear_bwd(int B, int Ci, int Co, int64_t N, const f
     hipLaunchKernelGGL(bwd_pointwise_kernel, dim3((unsigned)nblk), dim3(kThreads), lds, s, g, g, x,
                        (float*)nullptr, part, B, Ci, Co, (long long)N, 0, 0, 0.f);
     hipLaunchKernelGGL(reduce_partials_kernel, dim3((Co * Ci + Co + 63) / 64), dim3(64 * kRedGroups), 0, s,
-                       part, nblk, Co, Ci, gW, gb);
+                       part, nblk, Co, Ci, gW, gb, 0);
   }
   if (gx != nullptr) {
     float* wt = reinterpret_cast<float*>(part + (size_t)2048 * (Co * Ci + Co));

@@ -698,7 +698,7 @@ constexpr int kMixI = 4;
 __global__ __launch_bounds__(kThreads) void mix_bwd_kernel(
     const float2* __restrict__ xh, const float2* __restrict__ R, const float2* __restrict__ gh,
     float2* __restrict__ gR, float2* __restrict__ gxh, int B, int Ci, int Co, long long K, int mt,
-    int Nt, float invN) {
+    int Nt, float invN, int accumulate) {
   const long long k = (long long)blockIdx.x * kThreads + threadIdx.x;
   const int i0 = blockIdx.y * kMixI;
   if (k >= K) return;
@@ -719,7 +719,7 @@ __global__ __launch_bounds__(kThreads) void mix_bwd_kernel(
       for (int v = 0; v < kMixI; ++v) {
         const long long ridx = ((long long)(i0 + v) * Co + o) * K + k;
         r[v] = i0 + v < Ci ? R[ridx] : make_float2(0.f, 0.f);
-        gr[v] = (gR != nullptr && b0 > 0 && i0 + v < Ci) ? gR[ridx] : make_float2(0.f, 0.f);
+        gr[v] = (gR != nullptr && (b0 > 0 || accumulate) && i0 + v < Ci) ? gR[ridx] : make_float2(0.f, 0.f);
       }
 #pragma unroll
       for (int u = 0; u < kMixB; ++u) {
@@ -902,11 +902,11 @@ hipError_t launch_mix_fwd(const float2* xh, const float2* R, float2* yh, int B, 
 
 hipError_t launch_mix_bwd(const float2* xh, const float2* R, const float2* gh, float2* gR,
                           float2* gxh, int B, int Ci, int Co, int64_t K, int mt, int Nt,
-                          double invN, hipStream_t s) {
+                          double invN, int accumulate, hipStream_t s) {
   const int64_t nb = (K + kThreads - 1) / kThreads;
   if (nb > 0x7fffffffLL || Ci > 4 * 65535) return hipErrorInvalidValue;
   hipLaunchKernelGGL(mix_bwd_kernel, dim3((unsigned)nb, (unsigned)((Ci + kMixI - 1) / kMixI)), dim3(kThreads), 0, s, xh, R,
-                     gh, gR, gxh, B, Ci, Co, (long long)K, mt, Nt, (float)invN);
+                     gh, gR, gxh, B, Ci, Co, (long long)K, mt, Nt, (float)invN, accumulate);
   return hipGetLastError();
 }
 

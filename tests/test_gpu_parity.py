@@ -90,6 +90,9 @@ SMALL = [
     (2, 5, 4, (2, 2, 37, 16), (1, 1, 9, 8), 0),        # same, prime z length, ragged last row group, Cin != Cout
     (1, 2, 2, (3, 3, 35, 4), (1, 1, 6, 2), 1),         # same, three row tiles per block, symmetric rule
     (1, 2, 2, (2, 2, 135, 8), (1, 1, 30, 3), 0),       # dense forward z stage: two sweeps of row tiles, 15 of 16 columns
+    (1, 4, 4, (3, 5, 6, 7), (1, 2, 2, 3), 0),          # width 4 with 630 points (not a multiple of 64): the generic
+                                                       # backward pointwise kernel (erff / expf), where case 3 of the
+                                                       # same width takes the matrix-core one (rational erf)
 ]
 
 
@@ -160,6 +163,7 @@ def test_block_fwd_and_bwd_match_oracle(case, activation):
         # size of the summands (root-sum-square), elsewhere by the sum itself
         gb_scale = np.abs(ref["gb"]) + np.sqrt(np.sum(ref["gz"] ** 2, axis=(0, 2, 3, 4, 5)))
         assert np.max(np.abs(host(gb) - ref["gb"]) / np.maximum(gb_scale, 1e-300)) <= TOL
+        assert rel(host(gb), ref["gb"]) <= TOL          # and the criterion of every other tensor, as a vector
         # identical bits on a second run (fixed reduction order)
         gW2 = torch.empty_like(gW)
         gb2 = torch.empty_like(gb)
@@ -168,6 +172,40 @@ def test_block_fwd_and_bwd_match_oracle(case, activation):
                         dev(g_in), gx2, None, gW2, gb2, ws)
         torch.cuda.synchronize()
         assert torch.equal(gW, gW2) and torch.equal(gb, gb2) and torch.equal(gx, gx2)
+
+
+def test_accumulate_flag_adds_parameter_gradients_of_successive_calls():
+    """FNO_FLAG_ACCUMULATE_GRADS: gR, gW, gb of a second call are added to those of the first (the
+    gradient of a broadcast weight is a sum, Sec. 2.1), gx is overwritten; compared with the sum of
+    the oracle's gradients for the two cotangents."""
+    L = Layer(2, 4, 4, (8, 6, 16, 8), (2, 2, 4, 4), 0)
+    _, z, xh = gpu_block_fwd(L)
+    g1 = synth.normal_field(3, synth.T_GOUT, L.batch, L.c_out, L.spec.grid)
+    g2 = synth.normal_field(4, synth.T_GOUT, L.batch, L.c_out, L.spec.grid)
+    r1 = O.block_bwd(L.x, L.R, L.W, L.b, g1, L.spec, "gelu")
+    r2 = O.block_bwd(L.x, L.R, L.W, L.b, g2, L.spec, "gelu")
+    ws = B.alloc_workspace(L.desc, B.FNO_OP_BLOCK_BWD)
+    gx = torch.empty((L.batch, L.c_in) + L.spec.grid, device="cuda")
+    gR = torch.empty((L.c_in, L.c_out) + L.counts, dtype=torch.complex64, device="cuda")
+    gW = torch.empty((L.c_out, L.c_in), device="cuda")
+    gb = torch.empty((L.c_out,), device="cuda")
+    acc = B.make_desc(L.batch, L.c_in, L.c_out, L.spec.grid, L.spec.modes, L.spec.rule, B.FNO_ACT_GELU,
+                      B.FNO_FLAG_ACCUMULATE_GRADS)
+    B.fno_block_bwd(L.desc, dev(L.x), dev(L.R), dev(L.W), dev(z), dev(xh), dev(g1), gx, gR, gW, gb, ws)
+    B.fno_block_bwd(acc, dev(L.x), dev(L.R), dev(L.W), dev(z), dev(xh), dev(g2), gx, gR, gW, gb, ws)
+    torch.cuda.synchronize()
+    assert rel(host(gx), r2["gx"]) <= TOL
+    for name, got in (("gR", gR), ("gW", gW), ("gb", gb)):
+        assert rel(host(got), r1[name] + r2[name]) <= TOL, name
+    # the spectral convolution's own adjoint: gR accumulates, gx does not
+    ws2 = B.alloc_workspace(L.desc, B.FNO_OP_SPECTRAL_CONV_BWD)
+    gx1o, gR1o = O.spectral_conv_bwd(L.x, L.R, g1, L.spec)
+    gx2o, gR2o = O.spectral_conv_bwd(L.x, L.R, g2, L.spec)
+    B.fno_spectral_conv_bwd(L.desc, dev(L.x), None, dev(L.R), dev(g1), gx, gR, ws2)
+    B.fno_spectral_conv_bwd(acc, dev(L.x), None, dev(L.R), dev(g2), gx, gR, ws2)
+    torch.cuda.synchronize()
+    assert rel(host(gx), gx2o) <= TOL
+    assert rel(host(gR), gR1o + gR2o) <= TOL
 
 
 def test_spectral_branch_alone_is_not_masked_by_the_linear_term():

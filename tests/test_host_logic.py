@@ -128,3 +128,21 @@ def test_synthetic_inputs_are_reproducible_and_exact():
     assert np.array_equal(field.astype(np.float64), exact)
     r = synth.spectral_weights(0, 4, 4, (2, 2, 2, 3))
     assert r.dtype == np.complex64 and abs(np.std(r.real) - 0.25) < 0.05
+
+
+def test_binding_rejects_tensors_whose_size_does_not_match_the_descriptor():
+    """The kernels index by the descriptor alone; the binding refuses a mis-sized tensor on the host
+    (checked here with CPU tensors: the size check comes before the device check)."""
+    import pytest
+    import torch
+    desc = B.make_desc(1, 2, 2, (4, 4, 4, 4), (1, 1, 1, 2))
+    npts, kept = B._sizes(desc)
+    assert (npts, kept) == (256, 2 * 2 * 2 * 2)
+    good = torch.zeros((1, 2, 4, 4, 4, 4))
+    B._check_layer_tensors(desc, x=good, y=good, R=torch.zeros((2, 2, 2, 2, 2, 2), dtype=torch.complex64))
+    with pytest.raises(ValueError, match="x holds"):
+        B._check_layer_tensors(desc, x=torch.zeros((1, 2, 4, 4, 4, 3)), y=good)
+    with pytest.raises(ValueError, match="R holds"):
+        B._check_layer_tensors(desc, x=good, R=torch.zeros((2, 2, 2, 2, 2, 1), dtype=torch.complex64))
+    with pytest.raises(ValueError, match="xhat holds"):
+        B._check_layer_tensors(desc, x=good, xhat=torch.zeros((1, 2, 2, 2, 2, 3), dtype=torch.complex64))
