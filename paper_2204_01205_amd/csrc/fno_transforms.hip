@@ -512,36 +512,19 @@ __global__ __launch_bounds__(kThreads) void tz_fwd_fast_kernel(
     __syncthreads();
   }
 
-  // twiddle combine at the kept z-frequencies, all planes of the block in one index range; for the
-  // usual residue-class counts the terms of a sum are read together, then multiplied
-  const int per = Lz * mt, total = np * per;
-  const unsigned inv_per = 0xFFFFFFFFu / (unsigned)per + 1u;      // idx / per == umulhi(idx, inv_per) for idx < 2^16
-  auto combine = [&](auto pz_tag) {
-    constexpr int PZ = decltype(pz_tag)::value;                   // 0: taken from the argument
-    for (int idx = tid; idx < total; idx += nthr) {
-      const int p = (int)__umulhi((unsigned)idx, inv_per);
-      const int r = idx - p * per;
-      const int jz = (r * inv_mt) >> 16;
-      const int kt = r - jz * mt;
+  for (int p = 0; p < np; ++p) {
+    float2* dst = out + (plane0 + p) * (long long)(Lz * mt);
+    for (int idx = tid; idx < Lz * mt; idx += nthr) {
+      const int jz = (idx * inv_mt) >> 16;
+      const int kt = idx - jz * mt;
       const int mj = posmod(kfreq(jz, Lz, nposz), MZ);
       const float2* base = T + (p * mt + kt) * sT + (mj << pzshift);
       const float2* w = TW + (jz << pzshift);
       float2 acc = make_float2(0.f, 0.f);
-      if constexpr (PZ > 0) {
-        float2 wv[PZ], bv[PZ];
-#pragma unroll
-        for (int n2 = 0; n2 < PZ; ++n2) { wv[n2] = w[n2]; bv[n2] = base[n2]; }
-#pragma unroll
-        for (int n2 = 0; n2 < PZ; ++n2) acc = cfma(wv[n2], bv[n2], acc);
-      } else {
-        for (int n2 = 0; n2 < Pz; ++n2) acc = cfma(w[n2], base[n2], acc);
-      }
-      out[(plane0 + p) * (long long)per + r] = acc;
+      for (int n2 = 0; n2 < Pz; ++n2) acc = cfma(w[n2], base[n2], acc);
+      dst[idx] = acc;
     }
-  };
-  if (pzshift == 3) combine(std::integral_constant<int, 8>{});
-  else if (pzshift == 2) combine(std::integral_constant<int, 4>{});
-  else combine(std::integral_constant<int, 0>{});
+  }
 }
 
 // ------------------------------------------------------------------------------------------
@@ -808,9 +791,10 @@ hipError_t launch_tz_fwd(const float* x, float2* out, const float2* twt, const f
                     tz_fast_lds(az, Nt, mt, 1) <= (size_t)kLdsBudget;
   if (fast) {
     int ppb = 1;
-    // one plane of 128 rows per block: the smaller LDS share keeps more blocks resident, which hides
-    // the compute phases behind other blocks' loads a little better than two planes per block
-    while (ppb * 2 * az.N <= 128 && tz_fast_lds(az, Nt, mt, ppb * 2) <= (size_t)kLdsBudget) ppb *= 2;
+    // about 16 KB of input per block (one plane of 128 x 32, two of 128 x 16): the smaller LDS share
+    // keeps more blocks resident, which hides the compute phases behind other blocks' loads a little
+    // better than twice that, while smaller blocks than this lose to their fixed costs
+    while (ppb * 2 * az.N <= 256 && ppb * 2 * az.N * Nt <= 4096 && tz_fast_lds(az, Nt, mt, ppb * 2) <= (size_t)kLdsBudget) ppb *= 2;
     const int thr = ((ppb * az.N + 63) / 64) * 64;
     const size_t lds = tz_fast_lds(az, Nt, mt, ppb);
     const int region = tz_fast_region(az, Nt, mt, ppb);
