@@ -14,19 +14,21 @@ namespace {
 // (z stage, t stage, W part, epilogue), one per slot of u registers.  Slot s of lane block (wave, blk) is the quad
 // blk % 8 of row z = Pz (2 wave + blk / 8) + 2 step + s.  Launch: grid (NxNy, B), 512 threads.
 // The table blob is the one of zt_tables_kernel with Q = Pz (all twiddles, [Pz][Lz]).
-// MTC, LZC: the kept counts on t and z as compile-time constants (0: taken from the arguments), so
+// MTC, LZC, NPC: the kept counts on t and z (and how many of the latter are non-negative
+// frequencies) as compile-time constants (0: taken from the arguments), so
 // that the loops over them unroll; EPI >= 0 fixes the epilogue at compile time (bit 0: GELU, bit 1:
 // the pre-activation is stored as well), EPI = -1 reads it from the arguments.  With a fixed
 // epilogue every half step issues the same number of loads and stores on every path, which the
 // compiler's wait counts for the prefetched u values rely on.
-template <int CT, bool FULL, int MTC, int LZC, int EPI>
+template <int CT, bool FULL, int MTC, int LZC, int NPC, int EPI>
 __global__ __launch_bounds__(512, 4) void zt_inv_col_kernel(
     const float2* __restrict__ a, float* __restrict__ out, int Co_rt, int NxNy, int Nz, int Lz_rt,
-    int nposz, int mt_rt, int inv_mt, int a_floats, int a_stride4, int v_stride,
+    int nposz_rt, int mt_rt, int inv_mt, int a_floats, int a_stride4, int v_stride,
     const float* __restrict__ blob, int blob_floats, EpiArgs ep) {
   HIP_DYNAMIC_SHARED(float, smem)
   const int mt = MTC ? MTC : mt_rt;
   const int Lz = LZC ? LZC : Lz_rt;
+  const int nposz = LZC ? NPC : nposz_rt;      // first nposz stored frequencies are 0..nposz-1, the rest negative
   const bool act = EPI >= 0 ? (EPI & 1) != 0 : ep.act != 0;
   const bool zsave = EPI >= 0 ? (EPI & 2) != 0 : ep.zsave != nullptr;
   constexpr int NT = 32, MZ = 16, NW = 8;
@@ -289,19 +291,23 @@ hipError_t launch_zt_inv_col(const float2* a, float* out, const float2* twt, con
                                          Cu, 4 * CT, mt, Nt, Nt, az.L, az.P, az.P, blob_floats, s);
       if (terr != hipSuccess) return terr;
       const dim3 grid((unsigned)NxNy, (unsigned)B);
-#define FNO_ZTC(CTV, FULLV, MTV, LZV, EPIV)                                                            \
-  hipLaunchKernelGGL((zt_inv_col_kernel<CTV, FULLV, MTV, LZV, EPIV>), grid, dim3(512), lds, s, a, out, Co, \
+#define FNO_ZTC(CTV, FULLV, MTV, LZV, NPV, EPIV)                                                            \
+  hipLaunchKernelGGL((zt_inv_col_kernel<CTV, FULLV, MTV, LZV, NPV, EPIV>), grid, dim3(512), lds, s, a, out, Co, \
                      NxNy, az.N, az.L, az.npos, mt, inv_mt, a_floats, a_stride4, v_stride, tables,         \
                      blob_floats, e)
       // the shape of the large workloads (width 20, 9 kept t bins, 32 kept z frequencies) with its three
       // epilogues: forward, forward that keeps the pre-activation, and the adjoint's linear one
       const int epi = (e.act ? 1 : 0) | (e.zsave != nullptr ? 2 : 0);
-      if (CT == 5 && full && mt == 9 && az.L == 32 && e.u != nullptr && epi != 2) {
-        if (epi == 1) FNO_ZTC(5, true, 9, 32, 1);
-        else if (epi == 3) FNO_ZTC(5, true, 9, 32, 3);
-        else FNO_ZTC(5, true, 9, 32, 0);
-      } else if (CT == 2) { if (full) FNO_ZTC(2, true, 0, 0, -1); else FNO_ZTC(2, false, 0, 0, -1); }
-      else { if (full) FNO_ZTC(5, true, 0, 0, -1); else FNO_ZTC(5, false, 0, 0, -1); }
+      if (CT == 5 && full && mt == 9 && az.L == 32 && az.npos == 16 && e.u != nullptr && epi != 2) {
+        if (epi == 1) FNO_ZTC(5, true, 9, 32, 16, 1);
+        else if (epi == 3) FNO_ZTC(5, true, 9, 32, 16, 3);
+        else FNO_ZTC(5, true, 9, 32, 16, 0);
+      } else if (CT == 5 && full && mt == 9 && az.L == 24 && az.npos == 12 && e.u != nullptr && epi != 2) {
+        if (epi == 1) FNO_ZTC(5, true, 9, 24, 12, 1);
+        else if (epi == 3) FNO_ZTC(5, true, 9, 24, 12, 3);
+        else FNO_ZTC(5, true, 9, 24, 12, 0);
+      } else if (CT == 2) { if (full) FNO_ZTC(2, true, 0, 0, 0, -1); else FNO_ZTC(2, false, 0, 0, 0, -1); }
+      else { if (full) FNO_ZTC(5, true, 0, 0, 0, -1); else FNO_ZTC(5, false, 0, 0, 0, -1); }
 #undef FNO_ZTC
       *taken = true;
       return hipGetLastError();
