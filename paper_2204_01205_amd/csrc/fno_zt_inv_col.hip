@@ -98,15 +98,9 @@ __global__ __launch_bounds__(512, 4) void zt_inv_col_kernel(
         if (FULL || i < Cu) xv[i][sl] = ubase[i * Npts + sl * NT];
   }
   asm volatile("" ::: "memory");
-  // tables and spectrum have landed once at most the u loads, issued after them, are
-  // outstanding (the counter retires in order; vmcnt sits in bits 3:0 and 15:14)
-  if constexpr (FULL && 2 * CI < 64) {
-    constexpr int n = 2 * CI;
-    if (lin) __builtin_amdgcn_s_waitcnt(((n >> 4) << 14) | 0x0F70 | (n & 15));
-    else __builtin_amdgcn_s_waitcnt(0x0F70);
-  } else {
-    __builtin_amdgcn_s_waitcnt(0x0F70);
-  }
+  // everything issued so far has landed (the first u values too: the bias step below reads LDS that
+  // the LDS-direct loads write, and the compiler drains every load before such a read anyway)
+  __builtin_amdgcn_s_waitcnt(0x0F70);          // vmcnt(0)
   __syncthreads();
   // The bias rides on the spectrum: adding b[o] to the entry (kz = 0, kt = 0) of channel o (stored
   // first: j = 0, kt = 0) adds b[o] to every point of the channel (that entry's z twiddle and its

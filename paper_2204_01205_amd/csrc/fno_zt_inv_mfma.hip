@@ -95,7 +95,7 @@ __global__ __launch_bounds__(64 * NW, NW == 8 ? 4 : (CT >= 8 ? 2 : 3)) void zt_i
       __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(bsrc + c0 + 4 * lane),
                                        (__attribute__((address_space(3))) void*)(CS + c0), 16, 0, 0);
   }
-  asm volatile("" ::: "memory");    // keep the issue order: tables, tile, u (the wait below counts on it)
+  asm volatile("" ::: "memory");    // keep the issue order: tables, tile, u
   // the spectrum tile goes straight to LDS, 16 bytes per lane, channel by channel: the channel
   // stride in LDS (a_stride4 float4) is padded so that the z-stage reads, whose lanes differ in
   // (channel, kt), spread over the banks
@@ -127,15 +127,10 @@ __global__ __launch_bounds__(64 * NW, NW == 8 ? 4 : (CT >= 8 ? 2 : 3)) void zt_i
     }
   }
   asm volatile("" ::: "memory");
-  // wait for the table blob and the tile, not for the u loads (they were issued after them;
-  // the counter retires in order).  vmcnt sits in bits 3:0 and 15:14 of the immediate.
-  if constexpr (FULL && 2 * CI < 64) {
-    constexpr int n = 2 * CI;
-    if (lin) __builtin_amdgcn_s_waitcnt(((n >> 4) << 14) | 0x0F70 | (n & 15));
-    else __builtin_amdgcn_s_waitcnt(0x0F70);
-  } else {
-    __builtin_amdgcn_s_waitcnt(0x0F70);
-  }
+  // everything issued so far has landed.  (Waiting only for the tables and the tile, with the u
+  // loads still in flight over the z stage, needs a hand-counted vmcnt that depends on how many
+  // instructions the compiler emits for the u loads; it measured no faster, so the plain wait stays.)
+  __builtin_amdgcn_s_waitcnt(0x0F70);          // vmcnt(0)
   __syncthreads();
 
   // z stage: item (o, kt, q) collects the kept z-frequencies of one (channel, kt) column with
