@@ -844,7 +844,9 @@ hipError_t launch_tz_fwd(const float* x, float2* out, const float2* twt, const f
 hipError_t launch_axis_fwd(const float2* in, float2* out, const float2* tw, int64_t outer,
                            AxisPlan ax, int64_t inner, hipStream_t s) {
   if (outer <= 0 || inner <= 0) return hipSuccess;
-  const int W = axis_cols(ax, inner, ax.N, 16);
+  // the widest column tile the 32 KiB cap allows, up to 64 columns (16 for 256-point axes, 32 for
+  // 128, 64 below): more threads share the first, FFT phase, whose items are P x W
+  const int W = axis_cols(ax, inner, ax.N, 64);
   const int64_t ncb = (inner + W - 1) / W;
   const int64_t nblk = outer * ncb;
   if (nblk > 0x7fffffffLL || ncb > 0x7fffffffLL) return hipErrorInvalidValue;
@@ -860,7 +862,7 @@ hipError_t launch_axis_fwd(const float2* in, float2* out, const float2* tw, int6
 hipError_t launch_axis_inv(const float2* in, float2* out, const float2* tw, int64_t outer,
                            AxisPlan ax, int64_t inner, hipStream_t s) {
   if (outer <= 0 || inner <= 0) return hipSuccess;
-  const int W = axis_cols(ax, inner, ax.L, 32);
+  const int W = axis_cols(ax, inner, ax.L, 32);          // 16 and 64 columns both measured slower
   const int64_t ncb = (inner + W - 1) / W;
   const int64_t nblk = outer * ncb;
   if (nblk > 0x7fffffffLL || ncb > 0x7fffffffLL) return hipErrorInvalidValue;
