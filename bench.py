@@ -53,7 +53,7 @@ def cpu_baseline(cfg):
         threads = len(os.sched_getaffinity(0))
     grid = tuple(cfg["grid"])
     spec = O.LayerSpec(grid, tuple(cfg["modes"]), 0)
-    counts = synth.retained_counts(cfg["modes"])
+    counts = tuple(len(k) for k in O.mode_lists(spec))
     x = synth.normal_field(0, synth.T_X, 1, 1, grid)
     R = synth.spectral_weights(0, 1, 1, counts)
     W = synth.linear_weights(0, 1, 1)
@@ -131,7 +131,7 @@ def network_step_bench(args, torch, B, synth):
     cfg = synth.CONFIGS[args.config]
     batch, width, grid, modes = cfg["batch"], cfg["width"], tuple(cfg["grid"]), tuple(cfg["modes"])
     c_in, hidden, nblocks = cfg.get("in_channels", 5), cfg.get("hidden", 128), cfg.get("blocks", 4)
-    counts = synth.retained_counts(modes)
+    counts = B.kept_counts(B.make_desc(batch, width, width, grid, modes))
     npts = 1
     for n in grid:
         npts *= n
@@ -242,7 +242,7 @@ def main():
         return
     cfg = synth.CONFIGS[args.config]
     batch, width, grid, modes = cfg["batch"], cfg["width"], tuple(cfg["grid"]), tuple(cfg["modes"])
-    counts = synth.retained_counts(modes)
+    counts = B.kept_counts(B.make_desc(batch, width, width, grid, modes))
     npts = 1
     for n in grid:
         npts *= n

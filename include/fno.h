@@ -69,11 +69,16 @@ enum {
 enum {
   FNO_FLAG_MSE_TARGET = 1,       /* block_bwd: `gout` holds a target field; the upstream gradient is that of
                                     the mean squared error, 2 (sigma(z) - target) / (B Cout N)            */
-  FNO_FLAG_ACCUMULATE_GRADS = 2  /* block_bwd, spectral_conv_bwd: the parameter gradients (gR, gW, gb) are
+  FNO_FLAG_ACCUMULATE_GRADS = 2, /* block_bwd, spectral_conv_bwd: the parameter gradients (gR, gW, gb) are
                                     added to what the output buffers hold instead of overwriting them: the
                                     gradient of a broadcast weight is a sum (Sec. 2.1), and a step made of
                                     several calls (one per sample or per shard) continues that sum.  gx is
                                     always overwritten.                                                    */
+  FNO_FLAG_TABLES_READY = 4      /* every call with a workspace: the twiddle tables for this descriptor are in
+                                    `ws` already (written by fno_plan_tables on the same workspace, nothing
+                                    else having written there since except the library's own calls with the
+                                    same grid, modes and mode rule); the call then skips the four small
+                                    kernels that rebuild them                                              */
 };
 
 typedef struct {
@@ -89,6 +94,13 @@ typedef struct {
 
 /* Size in bytes of the workspace the given FNO_OP_* needs for this descriptor (host-only). */
 int fno_workspace_bytes(const fno_desc* desc, int op, size_t* bytes);
+
+/* Writes the twiddle tables of the transforms (Sec. 2.3: one truncated DFT per axis; they depend on
+ * the grid, the kept modes and the mode rule only) into the workspace, on `stream`.  Optional: every
+ * call rebuilds them itself unless its descriptor carries FNO_FLAG_TABLES_READY.  The table region
+ * sits at the same place in the workspace of every FNO_OP_*, so one plan serves all four calls on
+ * that workspace.  ws, ws_bytes as for the op given. */
+int fno_plan_tables(const fno_desc* desc, int op, void* ws, size_t ws_bytes, void* stream);
 
 /* Kept signed frequencies of axis 0..3 (x,y,z,t) in weight-tensor order (host-only).
  * out_k (host, nullable) receives *out_n values; out_n (host) receives the count. */

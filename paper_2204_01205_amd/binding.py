@@ -21,10 +21,11 @@ FNO_ACT_IDENTITY, FNO_ACT_GELU = 0, 1
 FNO_OP_SPECTRAL_CONV_FWD, FNO_OP_SPECTRAL_CONV_BWD, FNO_OP_BLOCK_FWD, FNO_OP_BLOCK_BWD = 0, 1, 2, 3
 FNO_FLAG_MSE_TARGET = 1
 FNO_FLAG_ACCUMULATE_GRADS = 2
+FNO_FLAG_TABLES_READY = 4
 FNO_STATIC_SCRATCH_BYTES = 64 << 20
 
 EXPORTS = [
-    "fno_workspace_bytes", "fno_mode_indices", "fno_spectral_conv_fwd", "fno_spectral_conv_bwd",
+    "fno_workspace_bytes", "fno_plan_tables", "fno_mode_indices", "fno_spectral_conv_fwd", "fno_spectral_conv_bwd",
     "fno_block_fwd", "fno_block_bwd", "fno_pointwise_linear", "fno_pointwise_mlp2", "fno_time_lift",
     "fno_rel_l2_workspace_bytes", "fno_rel_l2_loss", "fno_adam_step",
     "fno_pointwise_bwd_workspace_bytes", "fno_pointwise_linear_bwd", "fno_pointwise_mlp2_bwd",
@@ -145,12 +146,22 @@ def fno_workspace_bytes(desc: FnoDesc, op: int) -> int:
     return int(n.value)
 
 
+def fno_plan_tables(desc: FnoDesc, op: int, ws) -> None:
+    p, n = _ws(ws)
+    _check(lib().fno_plan_tables(ctypes.byref(desc), ctypes.c_int(op), p, n, _stream()))
+
+
 def fno_mode_indices(desc: FnoDesc, axis: int) -> list[int]:
     n = ctypes.c_int32(0)
     _check(lib().fno_mode_indices(ctypes.byref(desc), ctypes.c_int(axis), None, ctypes.byref(n)))
     buf = (ctypes.c_int32 * max(n.value, 1))()
     _check(lib().fno_mode_indices(ctypes.byref(desc), ctypes.c_int(axis), buf, ctypes.byref(n)))
     return [int(buf[i]) for i in range(n.value)]
+
+
+def kept_counts(desc: FnoDesc) -> tuple:
+    """Number of kept modes per axis (x, y, z, t): the lengths of the library's mode lists."""
+    return tuple(len(fno_mode_indices(desc, axis)) for axis in range(4))
 
 
 def alloc_workspace(desc: FnoDesc, op: int, device="cuda") -> torch.Tensor:

@@ -47,7 +47,7 @@ int make_plan(const fno_desc* d, bool need_block, bool need_bwd_block, Plan* p) 
   if (d->batch < 1 || d->c_in < 1 || d->c_out < 1) { set_detail("batch and channel widths must be >= 1"); return FNO_EINVAL; }
   if (d->mode_rule != 0 && d->mode_rule != 1) { set_detail("mode_rule must be 0 or 1"); return FNO_EINVAL; }
   if (d->activation != FNO_ACT_IDENTITY && d->activation != FNO_ACT_GELU) { set_detail("unknown activation"); return FNO_EINVAL; }
-  if (d->flags & ~(FNO_FLAG_MSE_TARGET | FNO_FLAG_ACCUMULATE_GRADS)) { set_detail("unknown flag bits"); return FNO_EINVAL; }
+  if (d->flags & ~(FNO_FLAG_MSE_TARGET | FNO_FLAG_ACCUMULATE_GRADS | FNO_FLAG_TABLES_READY)) { set_detail("unknown flag bits"); return FNO_EINVAL; }
   for (int a = 0; a < 4; ++a) {
     if (d->grid[a] < 1) { set_detail("grid sizes must be >= 1"); return FNO_EINVAL; }
     if (d->modes[a] < (a == 3 ? 1 : 0)) { set_detail("mode counts must be non-negative (mt >= 1)"); return FNO_EINVAL; }
@@ -177,7 +177,10 @@ void timing_end(hipStream_t s) {
 
 template <class T> T* at(void* ws, size_t off) { return reinterpret_cast<T*>(static_cast<char*>(ws) + off); }
 
-int build_tables(const Plan& p, void* ws, hipStream_t s) {
+// The twiddle tables depend on the descriptor only (grid, kept modes, mode rule).  tables_ready: the
+// caller states that fno_plan_tables wrote them into this workspace and nothing overwrote them.
+int build_tables(const Plan& p, void* ws, hipStream_t s, bool tables_ready = false) {
+  if (tables_ready) return FNO_OK;
   FNO_HIP(fno::launch_t_table(at<float2>(ws, p.off_twt), p.Nt, p.mt, s));
   for (int a = 0; a < 3; ++a) FNO_HIP(fno::launch_axis_table(at<float2>(ws, p.off_tw[a]), p.ax[a], s));
   return FNO_OK;
@@ -213,8 +216,8 @@ int inverse_chain(const Plan& p, void* ws, const float2* spec, int C, float* out
 }
 
 int conv_fwd_common(const Plan& p, const float* x, const float* R, float* out, float* xhat_save,
-                    void* ws, fno::Epilogue ep, hipStream_t s) {
-  int rc = build_tables(p, ws, s);
+                    void* ws, fno::Epilogue ep, bool tables_ready, hipStream_t s) {
+  int rc = build_tables(p, ws, s, tables_ready);
   if (rc != FNO_OK) return rc;
   float2* xh = xhat_save != nullptr ? reinterpret_cast<float2*>(xhat_save) : at<float2>(ws, p.off_s1);
   rc = forward_chain(p, ws, x, p.Ci, xh, s);
@@ -269,6 +272,17 @@ int fno_workspace_bytes(const fno_desc* desc, int op, size_t* bytes) {
   return FNO_OK;
 }
 
+int fno_plan_tables(const fno_desc* desc, int op, void* ws, size_t ws_bytes, void* stream) {
+  if (op < FNO_OP_SPECTRAL_CONV_FWD || op > FNO_OP_BLOCK_BWD) { set_detail("unknown op"); return FNO_EINVAL; }
+  Plan p;
+  const bool blk = (op == FNO_OP_BLOCK_FWD || op == FNO_OP_BLOCK_BWD);
+  int rc = make_plan(desc, blk, op == FNO_OP_BLOCK_BWD, &p);
+  if (rc != FNO_OK) return rc;
+  rc = check_ws(p, ws, ws_bytes);
+  if (rc != FNO_OK) return rc;
+  return build_tables(p, ws, static_cast<hipStream_t>(stream));
+}
+
 int fno_mode_indices(const fno_desc* desc, int axis, int32_t* out_k, int32_t* out_n) {
   if (out_n == nullptr) { set_detail("out_n is null"); return FNO_EINVAL; }
   if (axis < 0 || axis > 3) { set_detail("axis must be 0..3"); return FNO_EINVAL; }
@@ -292,7 +306,8 @@ int fno_spectral_conv_fwd(const fno_desc* desc, const float* x, const float* R, 
   rc = check_ws(p, ws, ws_bytes);
   if (rc != FNO_OK) return rc;
   fno::Epilogue ep{nullptr, 0, nullptr, 0, 0, nullptr, nullptr, 0};
-  return conv_fwd_common(p, x, R, y, xhat_save, ws, ep, static_cast<hipStream_t>(stream));
+  return conv_fwd_common(p, x, R, y, xhat_save, ws, ep, (desc->flags & FNO_FLAG_TABLES_READY) != 0,
+                         static_cast<hipStream_t>(stream));
 }
 
 int fno_spectral_conv_bwd(const fno_desc* desc, const float* x, const float* xhat_saved,
@@ -308,7 +323,7 @@ int fno_spectral_conv_bwd(const fno_desc* desc, const float* x, const float* xha
   if (rc != FNO_OK) return rc;
   if (gx == nullptr && gR == nullptr) return FNO_OK;
   hipStream_t s = static_cast<hipStream_t>(stream);
-  rc = build_tables(p, ws, s);
+  rc = build_tables(p, ws, s, (desc->flags & FNO_FLAG_TABLES_READY) != 0);
   if (rc != FNO_OK) return rc;
   fno::Epilogue ep{nullptr, 0, nullptr, 0, 0, nullptr, nullptr, 0};
   return conv_bwd_common(p, x, xhat_saved, R, gy, gx, gR, ws, ep, (desc->flags & FNO_FLAG_ACCUMULATE_GRADS) ? 1 : 0, s);
@@ -325,7 +340,8 @@ int fno_block_fwd(const fno_desc* desc, const float* x, const float* R, const fl
   rc = check_ws(p, ws, ws_bytes);
   if (rc != FNO_OK) return rc;
   fno::Epilogue ep{x, p.Ci, W, p.Ci, 1, b, z_save, desc->activation};
-  return conv_fwd_common(p, x, R, out, xhat_save, ws, ep, static_cast<hipStream_t>(stream));
+  return conv_fwd_common(p, x, R, out, xhat_save, ws, ep, (desc->flags & FNO_FLAG_TABLES_READY) != 0,
+                         static_cast<hipStream_t>(stream));
 }
 
 int fno_block_bwd(const fno_desc* desc, const float* x, const float* R, const float* W,
@@ -342,7 +358,7 @@ int fno_block_bwd(const fno_desc* desc, const float* x, const float* R, const fl
   rc = check_ws(p, ws, ws_bytes);
   if (rc != FNO_OK) return rc;
   hipStream_t s = static_cast<hipStream_t>(stream);
-  rc = build_tables(p, ws, s);
+  rc = build_tables(p, ws, s, (desc->flags & FNO_FLAG_TABLES_READY) != 0);
   if (rc != FNO_OK) return rc;
   float* gz = at<float>(ws, p.off_gz);
   double* part = at<double>(ws, p.off_part);

@@ -31,13 +31,6 @@ CONFIGS = {
 }
 
 
-def retained_counts(modes, rule=0):
-    """Number of kept indices per axis for a (mx,my,mz,mt) statement (shape bookkeeping only)."""
-    mx, my, mz, mt = modes
-    f = (lambda m: 2 * m) if rule == 0 else (lambda m: 2 * m + 1)
-    return (f(mx), f(my), f(mz), mt)
-
-
 def normal_slab(seed: int, tensor_id: int, b: int, c: int, grid, std: float = 1.0) -> np.ndarray:
     """float32 (Nx, Ny, Nz, Nt) ~ N(0, std^2): the (b, c) slab of normal_field(), on its own."""
     rng = np.random.default_rng([seed, tensor_id, b, c])

@@ -52,7 +52,7 @@ def setup(name, seed=5):
     c = synth.CONFIGS[name]
     grid, modes, width, batch = tuple(c["grid"]), tuple(c["modes"]), c["width"], c["batch"]
     spec = O.LayerSpec(grid, modes, 0)
-    counts = synth.retained_counts(modes)
+    counts = tuple(len(k) for k in O.mode_lists(spec))
     fx = synth.separable_factors(seed, batch, width, grid)
     R = synth.spectral_weights(seed, width, width, counts)
     W = synth.linear_weights(seed, width, width)

@@ -208,6 +208,35 @@ def test_accumulate_flag_adds_parameter_gradients_of_successive_calls():
     assert rel(host(gR), gR1o + gR2o) <= TOL
 
 
+def test_planned_tables_give_the_same_bits_as_rebuilt_ones():
+    """fno_plan_tables + FNO_FLAG_TABLES_READY: the calls skip their table kernels and return the
+    same bits, forward and backward, also after other calls used the workspace in between."""
+    L = Layer(2, 4, 4, (8, 6, 16, 8), (2, 2, 4, 4), 0)
+    out0, z0, xh0 = gpu_block_fwd(L)
+    flags = B.FNO_FLAG_TABLES_READY
+    ready = B.make_desc(L.batch, L.c_in, L.c_out, L.spec.grid, L.spec.modes, L.spec.rule, B.FNO_ACT_GELU, flags)
+    ws = B.alloc_workspace(ready, B.FNO_OP_BLOCK_BWD)
+    ws.fill_(0xFF)                                   # nothing usable in it before the plan
+    B.fno_plan_tables(ready, B.FNO_OP_BLOCK_BWD, ws)
+    out = torch.empty((L.batch, L.c_out) + L.spec.grid, device="cuda")
+    z = torch.empty_like(out)
+    xh = torch.empty((L.batch, L.c_in) + L.counts, dtype=torch.complex64, device="cuda")
+    gout = synth.normal_field(3, synth.T_GOUT, L.batch, L.c_out, L.spec.grid)
+    gx, gR = torch.empty_like(out), torch.empty((L.c_in, L.c_out) + L.counts, dtype=torch.complex64, device="cuda")
+    gW, gb = torch.empty((L.c_out, L.c_in), device="cuda"), torch.empty((L.c_out,), device="cuda")
+    ref = {}
+    for name, desc in (("rebuilt", L.desc), ("planned", ready), ("planned again", ready)):
+        B.fno_block_fwd(desc, dev(L.x), dev(L.R), dev(L.W), dev(L.b), out, z, xh, ws)
+        B.fno_block_bwd(desc, dev(L.x), dev(L.R), dev(L.W), z, xh, dev(gout), gx, gR, gW, gb, ws)
+        torch.cuda.synchronize()
+        got = [t.clone() for t in (out, z, torch.view_as_real(xh), gx, torch.view_as_real(gR), gW, gb)]
+        if not ref:
+            ref = got
+            assert np.array_equal(host(out), out0) and np.array_equal(host(z), z0)
+        else:
+            assert all(torch.equal(a, b) for a, b in zip(got, ref)), name
+
+
 def test_spectral_branch_alone_is_not_masked_by_the_linear_term():
     """The spectral term is much smaller than W x + b; zero W and b isolate it inside the block."""
     L = Layer(1, 4, 4, (16, 16, 32, 8), (4, 4, 8, 4))

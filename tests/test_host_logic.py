@@ -53,8 +53,7 @@ def test_workspace_sizes_and_config_table():
         sizes = [B.fno_workspace_bytes(d, op) for op in range(4)]
         assert all(s > 0 and s % 256 == 0 for s in sizes)
         assert sizes[3] > sizes[2] >= sizes[0]
-        counts = synth.retained_counts(c["modes"])
-        assert list(counts) == [len(k) for k in O.mode_lists(O.LayerSpec(c["grid"], c["modes"], 0))]
+        assert list(B.kept_counts(d)) == [len(k) for k in O.mode_lists(O.LayerSpec(c["grid"], c["modes"], 0))]
     # the largest workload's forward workspace stays far below one activation
     c = synth.CONFIGS["cfg4"]
     d = B.make_desc(1, 20, 20, c["grid"], c["modes"])
@@ -146,3 +145,16 @@ def test_binding_rejects_tensors_whose_size_does_not_match_the_descriptor():
         B._check_layer_tensors(desc, x=good, R=torch.zeros((2, 2, 2, 2, 2, 1), dtype=torch.complex64))
     with pytest.raises(ValueError, match="xhat holds"):
         B._check_layer_tensors(desc, x=good, xhat=torch.zeros((1, 2, 2, 2, 2, 3), dtype=torch.complex64))
+
+
+def test_plan_tables_checks_its_arguments_on_the_host():
+    import ctypes
+    desc = B.make_desc(1, 2, 2, (4, 4, 4, 4), (1, 1, 1, 2))
+    n = ctypes.c_size_t(B.fno_workspace_bytes(desc, B.FNO_OP_BLOCK_FWD))
+    null = ctypes.c_void_p(0)
+    assert B.lib().fno_plan_tables(ctypes.byref(desc), ctypes.c_int(B.FNO_OP_BLOCK_FWD), null, n, null) == B.FNO_EINVAL
+    assert B.lib().fno_plan_tables(ctypes.byref(desc), ctypes.c_int(9), null, n, null) == B.FNO_EINVAL
+    bad = B.make_desc(1, 2, 2, (4, 4, 4, 4), (3, 1, 1, 2))          # 6 kept modes on an axis of 4
+    assert B.lib().fno_plan_tables(ctypes.byref(bad), ctypes.c_int(B.FNO_OP_BLOCK_FWD), null, n, null) == B.FNO_EINVAL
+    misaligned = ctypes.c_void_p(64)
+    assert B.lib().fno_plan_tables(ctypes.byref(desc), ctypes.c_int(B.FNO_OP_BLOCK_FWD), misaligned, n, null) == B.FNO_ENOSPC

@@ -670,3 +670,37 @@ def test_whole_network_gradient_by_finite_differences():
     fd = (S(lw, blocks, (proj[0] + eps * d1,) + proj[1:]) - S(lw, blocks, (proj[0] - eps * d1,) + proj[1:])) / (2 * eps)
     an = float(np.sum(grads["proj"]["gW1"] * d1))
     assert abs(fd - an) <= 1e-8 + 1e-6 * abs(an)
+
+
+def test_fno_forward_is_the_chain_of_its_pinned_pieces():
+    """fno_forward against the chain written out with the separately pinned pieces (lift by explicit
+    sums, every block by block_fwd, projection by explicit sums): a dropped, repeated or reordered
+    block, or a block applied with another block's weights, changes the result."""
+    rng = np.random.default_rng(41)
+    grid, modes, width, hidden = (4, 3, 4, 6), (1, 1, 1, 3), 3, 5
+    spec = O.LayerSpec(grid, modes, 0)
+    counts = tuple(len(k) for k in O.mode_lists(spec))
+    a = rng.standard_normal((2, 2) + grid)
+    lw, lb = rng.standard_normal((width, 2)), rng.standard_normal(width)
+    blocks = [(rng.standard_normal((width, width) + counts) + 1j * rng.standard_normal((width, width) + counts),
+               rng.standard_normal((width, width)), rng.standard_normal(width)) for _ in range(3)]
+    w1, b1 = rng.standard_normal((hidden, width)), rng.standard_normal(hidden)
+    w2, b2 = rng.standard_normal((1, hidden)), rng.standard_normal(1)
+    got = O.fno_forward(a, lw, lb, blocks, (w1, b1, w2, b2), spec)
+
+    v = np.zeros((2, width) + grid)
+    for o in range(width):
+        v[:, o] = lb[o] + sum(lw[o, i] * a[:, i] for i in range(2))
+    for (r, w, b) in blocks:
+        v = O.block_fwd(v, r, w, b, spec, "gelu")[0]
+    h = np.zeros((2, hidden) + grid)
+    for k in range(hidden):
+        h[:, k] = b1[k] + sum(w1[k, i] * v[:, i] for i in range(width))
+    h = O.gelu(h)
+    want = b2[0] + sum(w2[0, k] * h[:, k] for k in range(hidden))
+    assert got.shape == (2, 1) + grid
+    assert np.max(np.abs(got[:, 0] - want)) <= 1e-12 * np.max(np.abs(want))
+    # the chain is sensitive to each block: leaving one out, or swapping two, moves the output
+    for other in (blocks[:2], [blocks[1], blocks[0], blocks[2]]):
+        alt = O.fno_forward(a, lw, lb, other, (w1, b1, w2, b2), spec)
+        assert np.max(np.abs(alt - got)) > 1e-3 * np.max(np.abs(got))

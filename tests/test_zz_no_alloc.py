@@ -23,7 +23,7 @@ def rel(a, b):
 
 
 def run_pair(seed, batch, width, grid, modes):
-    counts = synth.retained_counts(modes)
+    counts = tuple(len(k) for k in O.mode_lists(O.LayerSpec(grid, modes, 0)))
     x = synth.normal_field(seed, synth.T_X, batch, width, grid)
     R = synth.spectral_weights(seed, width, width, counts)
     desc = B.make_desc(batch, width, width, grid, modes, 0, B.FNO_ACT_IDENTITY)
@@ -57,7 +57,7 @@ def test_static_scratch_entry_point_refuses_shapes_beyond_the_array():
     grid, modes, width, batch = (64, 64, 64, 16), (12, 12, 12, 8), 20, 2
     desc = B.make_desc(batch, width, width, grid, modes, 0, B.FNO_ACT_IDENTITY)
     assert B.fno_workspace_bytes(desc, B.FNO_OP_SPECTRAL_CONV_FWD) > B.FNO_STATIC_SCRATCH_BYTES
-    counts = synth.retained_counts(modes)
+    counts = tuple(len(k) for k in O.mode_lists(O.LayerSpec(grid, modes, 0)))
     x = torch.zeros((batch, width) + grid, device="cuda")
     R = torch.zeros((width, width) + counts, dtype=torch.complex64, device="cuda")
     y = torch.full_like(x, 7.0)
