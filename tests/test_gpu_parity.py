@@ -237,6 +237,46 @@ def test_planned_tables_give_the_same_bits_as_rebuilt_ones():
             assert all(torch.equal(a, b) for a, b in zip(got, ref)), name
 
 
+@pytest.mark.parametrize("case", [(1, 8, 8, (2, 3, 128, 32), (1, 1, 16, 9), 0),      # column kernel
+                                  (2, 3, 3, (6, 5, 12, 6), (2, 2, 3, 4), 0)])        # generic kernels
+def test_block_forward_and_backward_replay_identically_from_a_hip_graph(case):
+    """The calls only enqueue kernels on the caller's stream (no allocation, no memset, no
+    synchronisation), so a caller may capture them in a HIP graph: three replays, with eager work and
+    synchronisations in between, each give the bits of the eager call."""
+    L = Layer(*case)
+    dx, dR, dW, db = dev(L.x), dev(L.R), dev(L.W), dev(L.b)
+    gout = dev(synth.normal_field(3, synth.T_GOUT, L.batch, L.c_out, L.spec.grid))
+    ws = B.alloc_workspace(L.desc, B.FNO_OP_BLOCK_BWD)
+    out = torch.empty((L.batch, L.c_out) + L.spec.grid, device="cuda")
+    z = torch.empty_like(out)
+    xh = torch.empty((L.batch, L.c_in) + L.counts, dtype=torch.complex64, device="cuda")
+    gx = torch.empty_like(out)
+    gR = torch.empty((L.c_in, L.c_out) + L.counts, dtype=torch.complex64, device="cuda")
+    gW, gb = torch.empty((L.c_out, L.c_in), device="cuda"), torch.empty((L.c_out,), device="cuda")
+    outs = (out, z, gx, gW, gb)
+
+    def step():
+        B.fno_block_fwd(L.desc, dx, dR, dW, db, out, z, xh, ws)
+        B.fno_block_bwd(L.desc, dx, dR, dW, z, xh, gout, gx, gR, gW, gb, ws)
+
+    step()
+    torch.cuda.synchronize()
+    eager = [t.clone() for t in outs] + [torch.view_as_real(xh).clone(), torch.view_as_real(gR).clone()]
+    graph = torch.cuda.CUDAGraph()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.graph(graph, stream=side):
+        step()
+    for _ in range(3):
+        for t in outs:
+            t.fill_(float("nan"))                    # eager work between the replays
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        got = list(outs) + [torch.view_as_real(xh), torch.view_as_real(gR)]
+        assert all(torch.equal(a, b) for a, b in zip(got, eager))
+
+
 def test_spectral_branch_alone_is_not_masked_by_the_linear_term():
     """The spectral term is much smaller than W x + b; zero W and b isolate it inside the block."""
     L = Layer(1, 4, 4, (16, 16, 32, 8), (4, 4, 8, 4))
