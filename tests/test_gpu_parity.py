@@ -351,6 +351,20 @@ def test_pointwise_lift_and_projection_and_small_network():
     assert rel(host(u), want) <= TOL
 
 
+@pytest.mark.parametrize("npts,ci,co", [(630, 5, 20), (632, 5, 20), (1024, 20, 1), (1026, 20, 1), (256, 3, 32)])
+def test_pointwise_linear_point_counts_and_widths(npts, ci, co):
+    """Point counts that are and are not multiples of 4 (16-byte and scalar kernels), all width classes."""
+    rng = np.random.default_rng(npts + co)
+    x = rng.standard_normal((2, ci, npts)).astype(np.float32)
+    w = synth.linear_weights(3, co, ci, synth.T_LIFT)
+    b = synth.bias(3, co, synth.T_LIFT)
+    y = torch.empty((2, co, npts), device="cuda")
+    B.fno_pointwise_linear(2, ci, co, npts, dev(x), dev(w), dev(b), y)
+    torch.cuda.synchronize()
+    want = O.pointwise_linear(x.reshape(2, ci, npts, 1, 1, 1), w, b).reshape(2, co, npts)
+    assert rel(host(y), want) <= TOL
+
+
 def test_block_against_the_stored_oracle_fixture():
     """The HIP path reproduces tests/golden/block_small.txt, values the float64 oracle wrote once.
 
