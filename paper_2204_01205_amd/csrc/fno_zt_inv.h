@@ -123,6 +123,9 @@ hipError_t launch_zt_tables(float* blob, int groups, const float2* twt, const fl
 hipError_t launch_zt_inv_col(const float2* a, float* out, const float2* twt, const float2* twz, int B, int Co,
                              int NxNy, AxisPlan az, int Nt, int mt, EpiArgs e, float* tables, hipStream_t s,
                              bool* taken);
+hipError_t launch_zt_inv_col16(const float2* a, float* out, const float2* twt, const float2* twz, int B, int Co,
+                               int NxNy, AxisPlan az, int Nt, int mt, EpiArgs e, float* tables, hipStream_t s,
+                               bool* taken);
 hipError_t launch_zt_inv_mfma(const float2* a, float* out, const float2* twt, const float2* twz, int B, int Co,
                               int NxNy, AxisPlan az, int Nt, int mt, EpiArgs e, float* tables, hipStream_t s,
                               bool* taken);

@@ -1,9 +1,10 @@
 // Inverse (z, t) stage of the transform chain (F^-1 of eq. (3) of arXiv 2204.01205 along the last
 // two axes, complex-to-real over t) fused with the pointwise part of the block update of eq. (2) /
-// Sec. 2.4, sigma(W x + b + K x).  Three kernels cover it, each in a translation unit of its own:
-// per column on the matrix cores (fno_zt_inv_col.hip), per tile on the matrix cores
+// Sec. 2.4, sigma(W x + b + K x).  Four kernels cover it, each in a translation unit of its own:
+// per column on the matrix cores (fno_zt_inv_col.hip for 32 points of t, fno_zt_inv_col16.hip for
+// 16), per tile on the matrix cores
 // (fno_zt_inv_mfma.hip) and the generic one (fno_zt_inv_generic.hip).  This file: the table blobs
-// the matrix-core kernels read and the choice between the three.
+// the matrix-core kernels read and the choice between them.
 #include "fno_zt_inv.h"
 
 namespace fno {
@@ -77,6 +78,8 @@ hipError_t launch_zt_inv(const float2* a, float* out, const float2* twt, const f
   if (aligned && tables != nullptr) {
     bool taken = false;
     hipError_t err = launch_zt_inv_col(a, out, twt, twz, B, Co, NxNy, az, Nt, mt, e, tables, s, &taken);
+    if (err != hipSuccess || taken) return err;
+    err = launch_zt_inv_col16(a, out, twt, twz, B, Co, NxNy, az, Nt, mt, e, tables, s, &taken);
     if (err != hipSuccess || taken) return err;
     err = launch_zt_inv_mfma(a, out, twt, twz, B, Co, NxNy, az, Nt, mt, e, tables, s, &taken);
     if (err != hipSuccess || taken) return err;

@@ -83,6 +83,11 @@ SMALL = [
     (1, 8, 8, (2, 3, 128, 32), (1, 1, 16, 9), 0),      # column kernel (Nt = 32): four steps per column
     (2, 3, 5, (3, 2, 64, 32), (1, 1, 6, 5), 0),        # same, padded channel tiles, Cin != Cout
     (1, 4, 4, (2, 2, 32, 32), (1, 1, 16, 17), 0),      # same, one step, every z and t mode kept
+    (1, 20, 20, (2, 3, 128, 16), (1, 1, 16, 9), 0),    # column kernel (Nt = 16): width 20 in two passes, two steps
+    (2, 20, 20, (2, 2, 64, 16), (1, 1, 12, 8), 0),     # same, one step, 24 kept z frequencies and 8 t bins
+    (1, 8, 8, (2, 3, 64, 16), (1, 1, 8, 5), 0),        # same, width 8: one pass
+    (2, 3, 5, (3, 2, 128, 16), (1, 1, 10, 7), 0),      # same, padded channel tiles, Cin != Cout
+    (1, 6, 6, (2, 2, 64, 16), (1, 1, 5, 4), 0),        # same, padded channel tiles in a block
     (1, 8, 8, (3, 2, 32, 30), (1, 1, 4, 8), 0),        # matrix-core inverse kernel, t axis padded 30 -> 32
     (2, 3, 3, (2, 3, 32, 12), (1, 1, 6, 4), 0),        # same, 12 -> 16, padded channel tiles
     (1, 20, 20, (2, 2, 64, 30), (1, 1, 12, 8), 0),     # same, width 20, the z and t lengths of the paper's samples
@@ -238,6 +243,7 @@ def test_planned_tables_give_the_same_bits_as_rebuilt_ones():
 
 
 @pytest.mark.parametrize("case", [(1, 8, 8, (2, 3, 128, 32), (1, 1, 16, 9), 0),      # column kernel
+                                  (1, 20, 20, (2, 3, 128, 16), (1, 1, 16, 9), 0),   # column kernel, Nt = 16
                                   (2, 3, 3, (6, 5, 12, 6), (2, 2, 3, 4), 0)])        # generic kernels
 def test_block_forward_and_backward_replay_identically_from_a_hip_graph(case):
     """The calls only enqueue kernels on the caller's stream (no allocation, no memset, no
