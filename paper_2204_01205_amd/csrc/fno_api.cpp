@@ -202,10 +202,14 @@ template <class T> T* at(void* ws, size_t off) { return reinterpret_cast<T*>(sta
 // caller states that fno_plan_tables wrote them into this workspace and nothing overwrote them.
 int build_tables(const Plan& p, void* ws, hipStream_t s, bool tables_ready = false) {
   if (tables_ready) return FNO_OK;
-  FNO_HIP(fno::launch_t_table(at<float2>(ws, p.off_twt), p.Nt, p.mt, s));
-  for (int a = 0; a < 3; ++a) FNO_HIP(fno::launch_axis_table(at<float2>(ws, p.off_tw[a]), p.ax[a], s));
+  fno::TableSet ts{};
+  ts.t[ts.n++] = fno::TableDesc{at<float2>(ws, p.off_twt), p.Nt, 0, p.mt, 1};
+  for (int a = 0; a < 3; ++a)
+    ts.t[ts.n++] = fno::TableDesc{at<float2>(ws, p.off_tw[a]), p.ax[a].N, p.ax[a].L, p.ax[a].npos, p.ax[a].P};
   for (int a = 0; a < 2; ++a)
-    if (p.off_twf[a] != p.off_tw[a]) FNO_HIP(fno::launch_axis_table(at<float2>(ws, p.off_twf[a]), p.axf[a], s));
+    if (p.off_twf[a] != p.off_tw[a])
+      ts.t[ts.n++] = fno::TableDesc{at<float2>(ws, p.off_twf[a]), p.axf[a].N, p.axf[a].L, p.axf[a].npos, p.axf[a].P};
+  FNO_HIP(fno::launch_plan_tables(ts, s));
   return FNO_OK;
 }
 

@@ -17,8 +17,11 @@ struct AxisPlan {
 
 // Fill the twiddle tables:  tw[j*P + n2] = exp(-2 pi i k_j n2 / N)  for an AxisPlan, and
 // twt[kt*Nt + n] = exp(-2 pi i kt n / Nt) for the real axis.
-hipError_t launch_axis_table(float2* tw, AxisPlan ax, hipStream_t s);
-hipError_t launch_t_table(float2* twt, int Nt, int mt, hipStream_t s);
+// Twiddle tables of a plan, written by one launch.  Axis table: L > 0, [L][P] entries
+// w_N^(k_j n2); t table: L = 0, [npos][N] entries w_N^(kt n).
+struct TableDesc { float2* tw; int N, L, npos, P; };
+struct TableSet { TableDesc t[6]; int n; };
+hipError_t launch_plan_tables(const TableSet& ts, hipStream_t s);
 
 // Forward (t, z): x[planes][Nz][Nt] real  ->  out[planes][Lz][mt] complex.
 hipError_t launch_tz_fwd(const float* x, float2* out, const float2* twt, const float2* twz,

@@ -21,26 +21,29 @@ namespace {
 // ------------------------------------------------------------------------------------------
 // Twiddle tables (double-precision sincospi, rounded once to float)
 // ------------------------------------------------------------------------------------------
-__global__ void axis_table_kernel(float2* tw, int N, int L, int npos, int P) {
+// All tables of a plan in one launch: blockIdx.y picks the table.  An axis table holds
+// w_N^(k_j n2) for the kept frequencies k_j and the residue classes n2 < P; the t table (L = 0)
+// holds w_Nt^(kt n) for kt < npos (= mt), n < N (= Nt).
+__global__ void plan_tables_kernel(TableSet ts) {
+  const TableDesc t = ts.t[blockIdx.y];
   const int idx = blockIdx.x * blockDim.x + threadIdx.x;
-  if (idx >= L * P) return;
-  const int j = idx / P, n2 = idx % P;
-  const long long k = kfreq(j, L, npos);
-  long long r = (k * n2) % N;
-  if (r < 0) r += N;
-  double s, c;
-  sincospi(-2.0 * double(r) / double(N), &s, &c);
-  tw[idx] = make_float2(float(c), float(s));
-}
-
-__global__ void t_table_kernel(float2* tw, int Nt, int mt) {
-  const int idx = blockIdx.x * blockDim.x + threadIdx.x;
-  if (idx >= Nt * mt) return;
-  const int kt = idx / Nt, n = idx % Nt;
-  const long long r = ((long long)kt * n) % Nt;
-  double s, c;
-  sincospi(-2.0 * double(r) / double(Nt), &s, &c);
-  tw[idx] = make_float2(float(c), float(s));
+  if (t.L > 0) {
+    if (idx >= t.L * t.P) return;
+    const int j = idx / t.P, n2 = idx % t.P;
+    const long long k = kfreq(j, t.L, t.npos);
+    long long r = (k * n2) % t.N;
+    if (r < 0) r += t.N;
+    double s, c;
+    sincospi(-2.0 * double(r) / double(t.N), &s, &c);
+    t.tw[idx] = make_float2(float(c), float(s));
+  } else {
+    if (idx >= t.N * t.npos) return;
+    const int kt = idx / t.N, n = idx % t.N;
+    const long long r = ((long long)kt * n) % t.N;
+    double s, c;
+    sincospi(-2.0 * double(r) / double(t.N), &s, &c);
+    t.tw[idx] = make_float2(float(c), float(s));
+  }
 }
 
 // ------------------------------------------------------------------------------------------
@@ -756,16 +759,14 @@ int axis_threads(int items) {
 bool tz_fwd_fits(AxisPlan az, int Nt, int mt) { return tz_fwd_lds(az, Nt, mt, 1) <= (size_t)kLdsBudget; }
 bool axis_fits(AxisPlan ax) { return (size_t)ax.N * 8 <= (size_t)(32 * 1024); }
 
-hipError_t launch_axis_table(float2* tw, AxisPlan ax, hipStream_t s) {
-  const int n = ax.L * ax.P;
-  hipLaunchKernelGGL(axis_table_kernel, dim3((n + 255) / 256), dim3(256), 0, s, tw, ax.N, ax.L,
-                     ax.npos, ax.P);
-  return hipGetLastError();
-}
-
-hipError_t launch_t_table(float2* twt, int Nt, int mt, hipStream_t s) {
-  const int n = Nt * mt;
-  hipLaunchKernelGGL(t_table_kernel, dim3((n + 255) / 256), dim3(256), 0, s, twt, Nt, mt);
+hipError_t launch_plan_tables(const TableSet& ts, hipStream_t s) {
+  if (ts.n <= 0) return hipSuccess;
+  int most = 1;
+  for (int i = 0; i < ts.n; ++i) {
+    const int n = ts.t[i].L > 0 ? ts.t[i].L * ts.t[i].P : ts.t[i].N * ts.t[i].npos;
+    if (n > most) most = n;
+  }
+  hipLaunchKernelGGL(plan_tables_kernel, dim3((most + 255) / 256, ts.n), dim3(256), 0, s, ts);
   return hipGetLastError();
 }
 
