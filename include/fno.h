@@ -238,7 +238,10 @@ int fno_spectral_conv_fwd_static(const fno_desc* desc, const float* x, const flo
 
 /* Benchmark hooks, outside the paper's layer: per-stage timing.  While enabled, every library call brackets each kernel it
  * launches with a pair of HIP events on the call's stream (events are created on first use and
- * kept).  fno_timing_read waits for the recorded events, returns up to `capacity` records in
+ * kept).  fno_timing_enable takes a mask of stages, bit (1 << FNO_STAGE_*) per stage, FNO_TIMING_ALL
+ * for every stage, 0 to switch timing off: an event pair costs a few microseconds of idle time
+ * between kernels, so a caller that times a whole step and wants one kernel's duration from the
+ * same run enables that stage alone.  fno_timing_read waits for the recorded events, returns up to `capacity` records in
  * launch order (stage id FNO_STAGE_*, elapsed milliseconds; host arrays) and clears the log.
  * This log is the library's only process-wide state and is not thread-safe; leave it disabled
  * under graph capture.  At most 8192 records are kept between reads. */
@@ -247,7 +250,8 @@ enum {
   FNO_STAGE_X_INV = 4, FNO_STAGE_Y_INV = 5, FNO_STAGE_ZT_INV = 6, FNO_STAGE_MIX_BWD = 7,
   FNO_STAGE_BWD_POINTWISE = 8
 };
-int fno_timing_enable(int on);
+#define FNO_TIMING_ALL (-1)
+int fno_timing_enable(int stage_mask);
 int fno_timing_read(int32_t* stages, float* ms, int32_t capacity, int32_t* count);
 
 /* Text for a status code; for FNO_EHIP / FNO_EUNSUPPORTED the calling thread's last detail. */

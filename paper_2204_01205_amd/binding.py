@@ -301,8 +301,20 @@ def fno_pointwise_mlp2(batch, c_in, hidden, c_out, npoints, x, W1, b1, W2, b2, y
                                     _ptr(b2, name="b2"), _ptr(y, name="y"), _stream()))
 
 
-def fno_timing_enable(on: bool) -> None:
-    _check(lib().fno_timing_enable(ctypes.c_int(1 if on else 0)))
+FNO_TIMING_ALL = -1
+
+
+def fno_timing_enable(stages) -> None:
+    """True: every stage; False: off; else stage names (as in STAGE_NAMES) to time alone."""
+    if stages is True:
+        mask = FNO_TIMING_ALL
+    elif not stages:
+        mask = 0
+    else:
+        mask = 0
+        for name in stages:
+            mask |= 1 << STAGE_NAMES.index(name)
+    _check(lib().fno_timing_enable(ctypes.c_int(mask)))
 
 
 def fno_timing_read(capacity: int = 8192):

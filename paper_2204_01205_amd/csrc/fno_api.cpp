@@ -166,12 +166,12 @@ int check_ws(const Plan& p, void* ws, size_t ws_bytes) {
 // ---- optional per-stage timing (benchmarks only) ------------------------------------------
 struct TimingRecord { int stage; hipEvent_t start, stop; };
 constexpr int kMaxTimingRecords = 8192;
-bool g_timing_on = false;
+int g_timing_mask = 0;        // bit per FNO_STAGE_*
 int g_timing_used = 0;
 std::vector<TimingRecord> g_timing;     // events are created once and reused
 
 bool timing_begin(int stage, hipStream_t s) {
-  if (!g_timing_on || g_timing_used >= kMaxTimingRecords) return false;
+  if (((g_timing_mask >> stage) & 1) == 0 || g_timing_used >= kMaxTimingRecords) return false;
   if (g_timing_used == (int)g_timing.size()) {
     TimingRecord r{stage, nullptr, nullptr};
     if (hipEventCreate(&r.start) != hipSuccess || hipEventCreate(&r.stop) != hipSuccess) return false;
@@ -515,8 +515,8 @@ int fno_adam_step(int64_t n, float* param, const float* grad, float* m, float* v
   return FNO_OK;
 }
 
-int fno_timing_enable(int on) {
-  g_timing_on = on != 0;
+int fno_timing_enable(int stage_mask) {
+  g_timing_mask = stage_mask;
   g_timing_used = 0;
   return FNO_OK;
 }
