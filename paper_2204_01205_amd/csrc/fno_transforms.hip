@@ -439,12 +439,20 @@ __device__ __forceinline__ void rfft_row_bins_r4(const float4 (&quads)[NT / 4], 
 // t stage spread over all banks; a wave's load still covers whole 128-byte lines.  The t-stage
 // results wait in registers over a barrier so the complex tile T can reuse the LDS of S.
 // Pz is a power of two and inv_mt = ceil(2^16 / mt) (shifts and a multiply instead of divisions).
-template <int NT, int MZ>
+// MTC, LZC, NPC, PZC, NTHR: the kept counts on t and z (and how many of the latter are
+// non-negative frequencies), log2 Pz and the block size as compile-time constants (0, or -1 for
+// PZC: taken from the arguments).  With them the per-bin guards of the t stage vanish and the
+// combine unrolls, its LDS reads going out together.
+template <int NT, int MZ, int MTC, int LZC, int NPC, int PZC, int NTHR>
 __global__ __launch_bounds__(kThreads) void tz_fwd_fast_kernel(
     const float* __restrict__ x, float2* __restrict__ out, const float2* __restrict__ twz,
-    long long planes, int Nz, int Lz, int nposz, int mt, int ppb, int region_floats, int pzshift,
+    long long planes, int Nz, int Lz_rt, int nposz_rt, int mt_rt, int ppb, int region_floats, int pzshift_rt,
     int inv_mt) {
   HIP_DYNAMIC_SHARED(float, smem)
+  const int mt = MTC ? MTC : mt_rt;
+  const int Lz = LZC ? LZC : Lz_rt;
+  const int nposz = LZC ? NPC : nposz_rt;
+  const int pzshift = PZC >= 0 ? PZC : pzshift_rt;
   constexpr int QPR = NT / 4;                  // quads per row
   constexpr int ROT = 16 / QPR > 0 ? 16 / QPR : 1;   // rows that share a rotation
   constexpr int H = NT / 2;
@@ -454,7 +462,7 @@ __global__ __launch_bounds__(kThreads) void tz_fwd_fast_kernel(
   float2* T = reinterpret_cast<float2*>(smem); // [ppb][mt][sT], same memory, later
   float2* TW = reinterpret_cast<float2*>(smem + region_floats);   // [Lz][Pz]
   const int tid = threadIdx.x;
-  const int nthr = blockDim.x;
+  const int nthr = NTHR ? NTHR : (int)blockDim.x;
   const int lane = tid & 63, wave = tid >> 6;
   const long long plane0 = (long long)blockIdx.x * ppb;
   const int np = (int)min((long long)ppb, planes - plane0);
@@ -517,15 +525,37 @@ __global__ __launch_bounds__(kThreads) void tz_fwd_fast_kernel(
 
   for (int p = 0; p < np; ++p) {
     float2* dst = out + (plane0 + p) * (long long)(Lz * mt);
-    for (int idx = tid; idx < Lz * mt; idx += nthr) {
-      const int jz = (idx * inv_mt) >> 16;
-      const int kt = idx - jz * mt;
-      const int mj = posmod(kfreq(jz, Lz, nposz), MZ);
-      const float2* base = T + (p * mt + kt) * sT + (mj << pzshift);
-      const float2* w = TW + (jz << pzshift);
-      float2 acc = make_float2(0.f, 0.f);
-      for (int n2 = 0; n2 < Pz; ++n2) acc = cfma(w[n2], base[n2], acc);
-      dst[idx] = acc;
+    if constexpr (MTC > 0 && LZC > 0 && PZC >= 0 && NTHR > 0) {
+      constexpr int PZ = 1 << PZC;
+#pragma unroll
+      for (int i0 = 0; i0 < LZC * MTC; i0 += NTHR) {
+        const int idx = i0 + tid;
+        if (i0 + NTHR <= LZC * MTC || idx < LZC * MTC) {
+          const int jz = idx / MTC;
+          const int kt = idx - jz * MTC;
+          const int mj = posmod(kfreq(jz, LZC, NPC), MZ);
+          const float2* base = T + (p * MTC + kt) * sT + (mj << PZC);
+          const float2* w = TW + (jz << PZC);
+          float2 wv[PZ], bv[PZ];
+#pragma unroll
+          for (int n2 = 0; n2 < PZ; ++n2) { wv[n2] = w[n2]; bv[n2] = base[n2]; }
+          float2 acc = make_float2(0.f, 0.f);
+#pragma unroll
+          for (int n2 = 0; n2 < PZ; ++n2) acc = cfma(wv[n2], bv[n2], acc);
+          dst[idx] = acc;
+        }
+      }
+    } else {
+      for (int idx = tid; idx < Lz * mt; idx += nthr) {
+        const int jz = (idx * inv_mt) >> 16;
+        const int kt = idx - jz * mt;
+        const int mj = posmod(kfreq(jz, Lz, nposz), MZ);
+        const float2* base = T + (p * mt + kt) * sT + (mj << pzshift);
+        const float2* w = TW + (jz << pzshift);
+        float2 acc = make_float2(0.f, 0.f);
+        for (int n2 = 0; n2 < Pz; ++n2) acc = cfma(w[n2], base[n2], acc);
+        dst[idx] = acc;
+      }
     }
   }
 }
@@ -802,18 +832,28 @@ hipError_t launch_tz_fwd(const float* x, float2* out, const float2* twt, const f
     const int64_t nblk = (planes + ppb - 1) / ppb;
     if (nblk > 0x7fffffffLL) return hipErrorInvalidValue;
     const int inv_mt = (65536 + mt - 1) / mt;
-#define FNO_TZF(NTV, MZV)                                                                     \
-  hipLaunchKernelGGL((tz_fwd_fast_kernel<NTV, MZV>), dim3((unsigned)nblk), dim3(thr), lds, s, \
-                     x, out, twz, (long long)planes, az.N, az.L, az.npos, mt, ppb, region,    \
+#define FNO_TZF_C(NTV, MZV, MTV, LZV, NPV, PZV, THRV)                                                         \
+  hipLaunchKernelGGL((tz_fwd_fast_kernel<NTV, MZV, MTV, LZV, NPV, PZV, THRV>), dim3((unsigned)nblk), dim3(thr), \
+                     lds, s, x, out, twz, (long long)planes, az.N, az.L, az.npos, mt, ppb, region,            \
                      ilog2(az.P), inv_mt)
+#define FNO_TZF(NTV, MZV) FNO_TZF_C(NTV, MZV, 0, 0, 0, -1, 0)
 #define FNO_TZF_M(NTV)                     \
   do {                                     \
     if (az.M == 8) FNO_TZF(NTV, 8);        \
     else FNO_TZF(NTV, 16);                 \
   } while (0)
-    if (Nt == 16) FNO_TZF_M(16); else if (Nt == 32) FNO_TZF_M(32); else FNO_TZF_M(64);
+    // the shapes of the named workloads as compile-time constants: 9 kept t bins with 32 kept z
+    // frequencies in 8 residue classes (z of 128 points), or 9 / 8 t bins with 24 in 4 classes (64)
+    const bool z128 = az.M == 16 && az.P == 8 && az.L == 32 && az.npos == 16 && mt == 9;
+    const bool z64 = az.M == 16 && az.P == 4 && az.L == 24 && az.npos == 12;
+    if (Nt == 32 && z128 && thr == 128) FNO_TZF_C(32, 16, 9, 32, 16, 3, 128);
+    else if (Nt == 16 && z128 && thr == 256) FNO_TZF_C(16, 16, 9, 32, 16, 3, 256);
+    else if (Nt == 32 && z64 && mt == 9 && thr == 128) FNO_TZF_C(32, 16, 9, 24, 12, 2, 128);
+    else if (Nt == 16 && z64 && mt == 8 && thr == 256) FNO_TZF_C(16, 16, 8, 24, 12, 2, 256);
+    else if (Nt == 16) FNO_TZF_M(16); else if (Nt == 32) FNO_TZF_M(32); else FNO_TZF_M(64);
 #undef FNO_TZF_M
 #undef FNO_TZF
+#undef FNO_TZF_C
     return hipGetLastError();
   }
   if (az.M == 1 && Nt % 4 == 0 && mt <= 16 && (reinterpret_cast<uintptr_t>(x) & 15) == 0) {
