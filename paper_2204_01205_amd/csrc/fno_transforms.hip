@@ -89,7 +89,8 @@ __global__ __launch_bounds__(kThreads) void tz_fwd_kernel(
   s_floats += (s_floats & 1);
   float2* T = reinterpret_cast<float2*>(smem + s_floats);   // [ppb][mt][sT]
   const int tid = threadIdx.x;
-  const long long plane0 = (long long)blockIdx.x * ppb;
+  const long long plane0 = xcd_contiguous_item(blockIdx.x, gridDim.x) * ppb;   // grid: a multiple of 8
+  if (plane0 >= planes) return;
   const int np = (int)min((long long)ppb, planes - plane0);
   const int plane_elems = Nz * Nt;
 
@@ -209,7 +210,8 @@ __global__ __launch_bounds__(kThreads) void tz_fwd_dense_kernel(
   // T's place once the sweep has read it (alias = 1), which halves the block's LDS
   float2* P = alias ? T : T + 16 * sT;
   const int tid = threadIdx.x, w = tid >> 6, lane = tid & 63, lr = lane & 15, lk = lane >> 4;
-  const long long plane0 = (long long)blockIdx.x * ppb;
+  const long long plane0 = xcd_contiguous_item(blockIdx.x, gridDim.x) * ppb;   // grid: a multiple of 8
+  if (plane0 >= planes) return;
   const int np = (int)min((long long)ppb, planes - plane0);
   const int ncol = np * mt;
 
@@ -464,7 +466,8 @@ __global__ __launch_bounds__(kThreads) void tz_fwd_fast_kernel(
   const int tid = threadIdx.x;
   const int nthr = NTHR ? NTHR : (int)blockDim.x;
   const int lane = tid & 63, wave = tid >> 6;
-  const long long plane0 = (long long)blockIdx.x * ppb;
+  const long long plane0 = xcd_contiguous_item(blockIdx.x, gridDim.x) * ppb;   // grid: a multiple of 8
+  if (plane0 >= planes) return;
   const int np = (int)min((long long)ppb, planes - plane0);
 
   {
@@ -829,7 +832,7 @@ hipError_t launch_tz_fwd(const float* x, float2* out, const float2* twt, const f
     const int thr = ((ppb * az.N + 63) / 64) * 64;
     const size_t lds = tz_fast_lds(az, Nt, mt, ppb);
     const int region = tz_fast_region(az, Nt, mt, ppb);
-    const int64_t nblk = (planes + ppb - 1) / ppb;
+    const int64_t nblk = (((planes + ppb - 1) / ppb + 7) / 8) * 8;
     if (nblk > 0x7fffffffLL) return hipErrorInvalidValue;
     const int inv_mt = (65536 + mt - 1) / mt;
 #define FNO_TZF_C(NTV, MZV, MTV, LZV, NPV, PZV, THRV)                                                         \
@@ -862,7 +865,7 @@ hipError_t launch_tz_fwd(const float* x, float2* out, const float2* twt, const f
     const size_t p_bytes = (size_t)(kThreads / 64) * kDenseMT * 16 * 16 * 8;
     const int alias = az.L <= kDenseMT * 16;      // one sweep: the partial sums reuse the rows' LDS
     const size_t lds = alias ? (t_bytes > p_bytes ? t_bytes : p_bytes) : t_bytes + p_bytes;
-    const int64_t nblk = (planes + ppb - 1) / ppb;
+    const int64_t nblk = (((planes + ppb - 1) / ppb + 7) / 8) * 8;
     if (nblk > 0x7fffffffLL) return hipErrorInvalidValue;
     if (lds <= (size_t)(150 * 1024)) {
       hipLaunchKernelGGL(tz_fwd_dense_kernel, dim3((unsigned)nblk), dim3(kThreads), lds, s, x, out, twt, twz,
@@ -874,7 +877,7 @@ hipError_t launch_tz_fwd(const float* x, float2* out, const float2* twt, const f
   // enough rows to occupy the block, within an LDS share that keeps several blocks per CU
   while (ppb * 2 * az.N <= 2 * kThreads && tz_fwd_lds(az, Nt, mt, ppb * 2) <= (size_t)(32 * 1024)) ppb *= 2;
   const size_t lds = tz_fwd_lds(az, Nt, mt, ppb);
-  const int64_t nblk = (planes + ppb - 1) / ppb;
+  const int64_t nblk = (((planes + ppb - 1) / ppb + 7) / 8) * 8;
   if (nblk > 0x7fffffffLL) return hipErrorInvalidValue;
   FNO_DISPATCH_M(az.M, hipLaunchKernelGGL((tz_fwd_kernel<MM>), dim3((unsigned)nblk), dim3(kThreads),
                                           lds, s, x, out, twt, twz, (long long)planes, az.N, Nt,
