@@ -10,6 +10,7 @@ namespace {
 
 constexpr int kThreads = 256;
 typedef float v4f __attribute__((ext_vector_type(4)));
+typedef float v2f __attribute__((ext_vector_type(2)));
 
 __device__ __forceinline__ int kfreq(int j, int L, int npos) { return j < npos ? j : j - L; }
 __device__ __forceinline__ int posmod(int a, int m) { int r = a % m; return r < 0 ? r + m : r; }
@@ -40,6 +41,16 @@ __device__ __forceinline__ float gelu_prime_f(float z) {
   const float cdf = 0.5f * (1.0f + erff(z * 0.70710678118654752440f));
   const float pdf = 0.39894228040143267794f * expf(-0.5f * z * z);
   return fmaf(z, pdf, cdf);
+}
+
+// Loads and stores of data that is touched once (streams much larger than the caches): the
+// nontemporal hint keeps them from displacing what other kernels and blocks reuse
+__device__ __forceinline__ float2 nt_load(const float2* p) {
+  const v2f v = __builtin_nontemporal_load(reinterpret_cast<const v2f*>(p));
+  return make_float2(v[0], v[1]);
+}
+__device__ __forceinline__ void nt_store(float2* p, float2 v) {
+  __builtin_nontemporal_store(v2f{v.x, v.y}, reinterpret_cast<v2f*>(p));
 }
 
 // Thread blocks are dealt to the chip's eight XCDs round robin.  For a grid padded to a multiple of

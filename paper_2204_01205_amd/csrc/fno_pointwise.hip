@@ -165,9 +165,12 @@ __global__ __launch_bounds__(kThreads) void bwd_pointwise_mfma_kernel(
 #pragma unroll
     for (int T = 0; T < CT; ++T) {
       const long long e = (bb * C + 4 * T + j4) * N + p0;
-      const float4 zv = *reinterpret_cast<const float4*>(z + e);
-      float4 g = *reinterpret_cast<const float4*>(gout + e);
-      xv[T] = *reinterpret_cast<const float4*>(x + e);
+      const v4f zq = __builtin_nontemporal_load(reinterpret_cast<const v4f*>(z + e));
+      const v4f gq = __builtin_nontemporal_load(reinterpret_cast<const v4f*>(gout + e));
+      const v4f xq = __builtin_nontemporal_load(reinterpret_cast<const v4f*>(x + e));
+      const float4 zv = make_float4(zq[0], zq[1], zq[2], zq[3]);
+      float4 g = make_float4(gq[0], gq[1], gq[2], gq[3]);
+      xv[T] = make_float4(xq[0], xq[1], xq[2], xq[3]);
       if (act) {
         float v0, v1, v2, v3, d0, d1, d2, d3;
         gelu_and_grad_f(zv.x, v0, d0); gelu_and_grad_f(zv.y, v1, d1);
@@ -179,7 +182,7 @@ __global__ __launch_bounds__(kThreads) void bwd_pointwise_mfma_kernel(
         g = make_float4(mse_scale * (zv.x - g.x), mse_scale * (zv.y - g.y), mse_scale * (zv.z - g.z),
                         mse_scale * (zv.w - g.w));
       }
-      *reinterpret_cast<float4*>(gz_out + e) = g;
+      __builtin_nontemporal_store(v4f{g.x, g.y, g.z, g.w}, reinterpret_cast<v4f*>(gz_out + e));
       gbacc[T] += (g.x + g.y) + (g.z + g.w);
       gzv[T] = g;
     }

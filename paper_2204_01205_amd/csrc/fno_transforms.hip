@@ -478,7 +478,7 @@ __global__ __launch_bounds__(kThreads) void tz_fwd_fast_kernel(
       const int zl = p4 / QPR, sl = p4 - zl * QPR;
       const int q = (sl - zl / ROT) & (QPR - 1);
       __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(src + zl * QPR + q),
-                                       (__attribute__((address_space(3))) void*)(S + 4 * c0), 16, 0, 0);
+                                       (__attribute__((address_space(3))) void*)(S + 4 * c0), 16, 0, 2);   // aux 2: nontemporal
     }
     const float4* tsrc = reinterpret_cast<const float4*>(twz);
     const int tw4 = (Lz << pzshift) >> 1;      // float4 pieces of the twiddle table (Lz * Pz even)
@@ -545,7 +545,7 @@ __global__ __launch_bounds__(kThreads) void tz_fwd_fast_kernel(
           float2 acc = make_float2(0.f, 0.f);
 #pragma unroll
           for (int n2 = 0; n2 < PZ; ++n2) acc = cfma(wv[n2], bv[n2], acc);
-          dst[idx] = acc;
+          nt_store(&dst[idx], acc);
         }
       }
     } else {
@@ -557,7 +557,7 @@ __global__ __launch_bounds__(kThreads) void tz_fwd_fast_kernel(
         const float2* w = TW + (jz << pzshift);
         float2 acc = make_float2(0.f, 0.f);
         for (int n2 = 0; n2 < Pz; ++n2) acc = cfma(w[n2], base[n2], acc);
-        dst[idx] = acc;
+        nt_store(&dst[idx], acc);
       }
     }
   }
@@ -588,7 +588,7 @@ __global__ __launch_bounds__(kThreads) void axis_fwd_kernel(
       const float2* src = in + (o * N + n2) * inner + c0 + col;
       float2 a[M];
 #pragma unroll
-      for (int n1 = 0; n1 < M; ++n1) a[n1] = src[(long long)(P * n1) * inner];
+      for (int n1 = 0; n1 < M; ++n1) a[n1] = nt_load(&src[(long long)(P * n1) * inner]);
       fft_reg<M, -1>(a);
 #pragma unroll
       for (int m = 0; m < M; ++m) F[(P * m + n2) * W + col] = a[bitrev<M>(m)];
@@ -656,7 +656,7 @@ __global__ __launch_bounds__(kThreads) void axis_inv_kernel(
       fft_reg<M, +1>(g);
       float2* dst = out + (o * N + n2) * inner + c0 + col;
 #pragma unroll
-      for (int n1 = 0; n1 < M; ++n1) dst[(long long)(P * n1) * inner] = g[bitrev<M>(n1)];
+      for (int n1 = 0; n1 < M; ++n1) nt_store(&dst[(long long)(P * n1) * inner], g[bitrev<M>(n1)]);
     }
   }
 }
@@ -696,7 +696,7 @@ __global__ __launch_bounds__(kThreads) void mix_fwd_kernel(
 #pragma unroll
       for (int v = 0; v < KO; ++v) {
         if (o0 + v < Co) {
-          const float2 r = R[((long long)i * Co + o0 + v) * K + k];
+          const float2 r = nt_load(&R[((long long)i * Co + o0 + v) * K + k]);
 #pragma unroll
           for (int u = 0; u < KB; ++u) acc[u][v] = cfma(xv[u], r, acc[u][v]);
         }
@@ -737,7 +737,7 @@ __global__ __launch_bounds__(kThreads) void mix_bwd_kernel(
 #pragma unroll
       for (int v = 0; v < kMixI; ++v) {
         const long long ridx = ((long long)(i0 + v) * Co + o) * K + k;
-        r[v] = i0 + v < Ci ? R[ridx] : make_float2(0.f, 0.f);
+        r[v] = i0 + v < Ci ? nt_load(&R[ridx]) : make_float2(0.f, 0.f);
         gr[v] = (gR != nullptr && (b0 > 0 || accumulate) && i0 + v < Ci) ? gR[ridx] : make_float2(0.f, 0.f);
       }
 #pragma unroll
@@ -755,7 +755,7 @@ __global__ __launch_bounds__(kThreads) void mix_bwd_kernel(
       if (gR != nullptr) {
 #pragma unroll
         for (int v = 0; v < kMixI; ++v)
-          if (i0 + v < Ci) gR[((long long)(i0 + v) * Co + o) * K + k] = gr[v];
+          if (i0 + v < Ci) nt_store(&gR[((long long)(i0 + v) * Co + o) * K + k], gr[v]);
       }
     }
     if (gxh != nullptr) {

@@ -95,7 +95,7 @@ __global__ __launch_bounds__(512, 4) void zt_inv_col_kernel(
     for (int sl = 0; sl < 2; ++sl)
 #pragma unroll
       for (int i = 0; i < CI; ++i)
-        if (FULL || i < Cu) xv[i][sl] = ubase[i * Npts + sl * NT];
+        if (FULL || i < Cu) xv[i][sl] = __builtin_nontemporal_load(&ubase[i * Npts + sl * NT]);
   }
   asm volatile("" ::: "memory");
   // everything issued so far has landed (the first u values too: the bias step below reads LDS that
@@ -228,7 +228,7 @@ __global__ __launch_bounds__(512, 4) void zt_inv_col_kernel(
         if constexpr (PREFETCH) {
 #pragma unroll
           for (int i = 0; i < CI; ++i)
-            if (FULL || i < Cu) xv[i][sl] = ubase[i * Npts + (n2 + 2) * NT];
+            if (FULL || i < Cu) xv[i][sl] = __builtin_nontemporal_load(&ubase[i * Npts + (n2 + 2) * NT]);
         }
         asm volatile("" ::: "memory");
       }
@@ -239,20 +239,19 @@ __global__ __launch_bounds__(512, 4) void zt_inv_col_kernel(
 #pragma unroll
         for (int T = 0; T < CT; ++T)
           if (FULL || 4 * T + j4 < Co)
-            *reinterpret_cast<float4*>(zp + (4 * T) * Npts) = make_float4(acc[T][0], acc[T][1], acc[T][2], acc[T][3]);
+            __builtin_nontemporal_store(acc[T], reinterpret_cast<v4f*>(zp + (4 * T) * Npts));
       }
       if (act) {
 #pragma unroll
         for (int T = 0; T < CT; ++T)
           if (FULL || 4 * T + j4 < Co)
-            *reinterpret_cast<float4*>(op + (4 * T) * Npts) =
-                make_float4(gelu_fast_f(acc[T][0]), gelu_fast_f(acc[T][1]), gelu_fast_f(acc[T][2]),
-                            gelu_fast_f(acc[T][3]));
+            __builtin_nontemporal_store(v4f{gelu_fast_f(acc[T][0]), gelu_fast_f(acc[T][1]), gelu_fast_f(acc[T][2]),
+                                            gelu_fast_f(acc[T][3])}, reinterpret_cast<v4f*>(op + (4 * T) * Npts));
       } else {
 #pragma unroll
         for (int T = 0; T < CT; ++T)
           if (FULL || 4 * T + j4 < Co)
-            *reinterpret_cast<float4*>(op + (4 * T) * Npts) = make_float4(acc[T][0], acc[T][1], acc[T][2], acc[T][3]);
+            __builtin_nontemporal_store(acc[T], reinterpret_cast<v4f*>(op + (4 * T) * Npts));
       }
     }
   };
