@@ -778,13 +778,14 @@ __global__ __launch_bounds__(kThreads) void adam_kernel(
     float* __restrict__ v, float lr, float beta1, float omb1, float beta2, float omb2, float eps, float c1,
     float c2) {
   // omb = 1 - beta, rounded from double on the host (1 - beta in float would lose five digits)
+  // every element is read and written once per step: nontemporal accesses
   for (long long i = (long long)blockIdx.x * kThreads + threadIdx.x; i < n; i += (long long)gridDim.x * kThreads) {
-    const float gi = g[i];
-    const float mi = fmaf(beta1, m[i], omb1 * gi);
-    const float vi = fmaf(beta2, v[i], omb2 * gi * gi);
-    m[i] = mi;
-    v[i] = vi;
-    p[i] -= lr * (mi * c1) / (sqrtf(vi * c2) + eps);
+    const float gi = __builtin_nontemporal_load(g + i);
+    const float mi = fmaf(beta1, __builtin_nontemporal_load(m + i), omb1 * gi);
+    const float vi = fmaf(beta2, __builtin_nontemporal_load(v + i), omb2 * gi * gi);
+    __builtin_nontemporal_store(mi, m + i);
+    __builtin_nontemporal_store(vi, v + i);
+    __builtin_nontemporal_store(__builtin_nontemporal_load(p + i) - lr * (mi * c1) / (sqrtf(vi * c2) + eps), p + i);
   }
 }
 
