@@ -43,14 +43,30 @@ __device__ __forceinline__ float gelu_prime_f(float z) {
   return fmaf(z, pdf, cdf);
 }
 
-// Loads and stores of data that is touched once (streams much larger than the caches): the
-// nontemporal hint keeps them from displacing what other kernels and blocks reuse
-__device__ __forceinline__ float2 nt_load(const float2* p) {
-  const v2f v = __builtin_nontemporal_load(reinterpret_cast<const v2f*>(p));
+// Loads and stores of data that a kernel touches once.  STREAM: with the nontemporal hint, so that
+// a stream much larger than the caches does not displace what other kernels and blocks reuse.  The
+// launchers set it for tensors above kStreamBytes; below that the whole working set can live in the
+// 256 MB memory-side cache from one kernel to the next, and the hint would throw that away
+// (measured: +16 % on a block forward whose tensors are 84 MB, -4..-5 % from 335 MB up).
+constexpr long long kStreamBytes = 256ll << 20;
+template <bool STREAM, class T>
+__device__ __forceinline__ T ld_once(const T* p) {
+  if constexpr (STREAM) return __builtin_nontemporal_load(p);
+  else return *p;
+}
+template <bool STREAM, class T>
+__device__ __forceinline__ void st_once(T* p, T v) {
+  if constexpr (STREAM) __builtin_nontemporal_store(v, p);
+  else *p = v;
+}
+template <bool STREAM>
+__device__ __forceinline__ float2 ld_once2(const float2* p) {
+  const v2f v = ld_once<STREAM>(reinterpret_cast<const v2f*>(p));
   return make_float2(v[0], v[1]);
 }
-__device__ __forceinline__ void nt_store(float2* p, float2 v) {
-  __builtin_nontemporal_store(v2f{v.x, v.y}, reinterpret_cast<v2f*>(p));
+template <bool STREAM>
+__device__ __forceinline__ void st_once2(float2* p, float2 v) {
+  st_once<STREAM>(reinterpret_cast<v2f*>(p), v2f{v.x, v.y});
 }
 
 // Thread blocks are dealt to the chip's eight XCDs round robin.  For a grid padded to a multiple of

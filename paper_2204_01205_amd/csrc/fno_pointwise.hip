@@ -129,7 +129,7 @@ __device__ __forceinline__ void gelu_and_grad_f(float z, float& val, float& grad
   grad = fmaf(z, pdf, cdf);
 }
 
-template <int CT>
+template <int CT, bool STREAM>
 __global__ __launch_bounds__(kThreads) void bwd_pointwise_mfma_kernel(
     const float* __restrict__ z, const float* __restrict__ gout, const float* __restrict__ x,
     float* __restrict__ gz_out, double* __restrict__ part, int B, long long N, int act, int mse_target,
@@ -165,9 +165,9 @@ __global__ __launch_bounds__(kThreads) void bwd_pointwise_mfma_kernel(
 #pragma unroll
     for (int T = 0; T < CT; ++T) {
       const long long e = (bb * C + 4 * T + j4) * N + p0;
-      const v4f zq = __builtin_nontemporal_load(reinterpret_cast<const v4f*>(z + e));
-      const v4f gq = __builtin_nontemporal_load(reinterpret_cast<const v4f*>(gout + e));
-      const v4f xq = __builtin_nontemporal_load(reinterpret_cast<const v4f*>(x + e));
+      const v4f zq = ld_once<STREAM>(reinterpret_cast<const v4f*>(z + e));
+      const v4f gq = ld_once<STREAM>(reinterpret_cast<const v4f*>(gout + e));
+      const v4f xq = ld_once<STREAM>(reinterpret_cast<const v4f*>(x + e));
       const float4 zv = make_float4(zq[0], zq[1], zq[2], zq[3]);
       float4 g = make_float4(gq[0], gq[1], gq[2], gq[3]);
       xv[T] = make_float4(xq[0], xq[1], xq[2], xq[3]);
@@ -182,7 +182,7 @@ __global__ __launch_bounds__(kThreads) void bwd_pointwise_mfma_kernel(
         g = make_float4(mse_scale * (zv.x - g.x), mse_scale * (zv.y - g.y), mse_scale * (zv.z - g.z),
                         mse_scale * (zv.w - g.w));
       }
-      __builtin_nontemporal_store(v4f{g.x, g.y, g.z, g.w}, reinterpret_cast<v4f*>(gz_out + e));
+      st_once<STREAM>(reinterpret_cast<v4f*>(gz_out + e), v4f{g.x, g.y, g.z, g.w});
       gbacc[T] += (g.x + g.y) + (g.z + g.w);
       gzv[T] = g;
     }
@@ -1008,11 +1008,16 @@ hipError_t launch_bwd_pointwise(const float* z, const float* gout, const float* 
     if (nb > 1024) nb = 1024;
     *nslots = (int)nb * 4;
     const dim3 grid((unsigned)nb);
+    const bool stream = (int64_t)B * Co * N * 4 >= kStreamBytes;      // each tensor is touched once
     switch (Co / 4) {
 #define FNO_BPW(CTV)                                                                               \
   case CTV:                                                                                        \
-    hipLaunchKernelGGL((bwd_pointwise_mfma_kernel<CTV>), grid, dim3(kThreads), 0, s, z, gout, x,   \
-                       gz_out, part, B, (long long)N, act, mse_target, (float)mse_scale);          \
+    if (stream)                                                                                    \
+      hipLaunchKernelGGL((bwd_pointwise_mfma_kernel<CTV, true>), grid, dim3(kThreads), 0, s, z, gout, x,  \
+                         gz_out, part, B, (long long)N, act, mse_target, (float)mse_scale);        \
+    else                                                                                           \
+      hipLaunchKernelGGL((bwd_pointwise_mfma_kernel<CTV, false>), grid, dim3(kThreads), 0, s, z, gout, x, \
+                         gz_out, part, B, (long long)N, act, mse_target, (float)mse_scale);        \
     break;
       FNO_BPW(1) FNO_BPW(2) FNO_BPW(3) FNO_BPW(4) FNO_BPW(5)
 #undef FNO_BPW

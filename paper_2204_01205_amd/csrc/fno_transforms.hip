@@ -445,7 +445,7 @@ __device__ __forceinline__ void rfft_row_bins_r4(const float4 (&quads)[NT / 4], 
 // non-negative frequencies), log2 Pz and the block size as compile-time constants (0, or -1 for
 // PZC: taken from the arguments).  With them the per-bin guards of the t stage vanish and the
 // combine unrolls, its LDS reads going out together.
-template <int NT, int MZ, int MTC, int LZC, int NPC, int PZC, int NTHR>
+template <int NT, int MZ, int MTC, int LZC, int NPC, int PZC, int NTHR, bool STREAM>
 __global__ __launch_bounds__(kThreads) void tz_fwd_fast_kernel(
     const float* __restrict__ x, float2* __restrict__ out, const float2* __restrict__ twz,
     long long planes, int Nz, int Lz_rt, int nposz_rt, int mt_rt, int ppb, int region_floats, int pzshift_rt,
@@ -478,7 +478,7 @@ __global__ __launch_bounds__(kThreads) void tz_fwd_fast_kernel(
       const int zl = p4 / QPR, sl = p4 - zl * QPR;
       const int q = (sl - zl / ROT) & (QPR - 1);
       __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(src + zl * QPR + q),
-                                       (__attribute__((address_space(3))) void*)(S + 4 * c0), 16, 0, 2);   // aux 2: nontemporal
+                                       (__attribute__((address_space(3))) void*)(S + 4 * c0), 16, 0, STREAM ? 2 : 0);   // aux 2: nontemporal
     }
     const float4* tsrc = reinterpret_cast<const float4*>(twz);
     const int tw4 = (Lz << pzshift) >> 1;      // float4 pieces of the twiddle table (Lz * Pz even)
@@ -545,7 +545,7 @@ __global__ __launch_bounds__(kThreads) void tz_fwd_fast_kernel(
           float2 acc = make_float2(0.f, 0.f);
 #pragma unroll
           for (int n2 = 0; n2 < PZ; ++n2) acc = cfma(wv[n2], bv[n2], acc);
-          nt_store(&dst[idx], acc);
+          st_once2<STREAM>(&dst[idx], acc);
         }
       }
     } else {
@@ -557,7 +557,7 @@ __global__ __launch_bounds__(kThreads) void tz_fwd_fast_kernel(
         const float2* w = TW + (jz << pzshift);
         float2 acc = make_float2(0.f, 0.f);
         for (int n2 = 0; n2 < Pz; ++n2) acc = cfma(w[n2], base[n2], acc);
-        nt_store(&dst[idx], acc);
+        st_once2<STREAM>(&dst[idx], acc);
       }
     }
   }
@@ -566,7 +566,7 @@ __global__ __launch_bounds__(kThreads) void tz_fwd_fast_kernel(
 // ------------------------------------------------------------------------------------------
 // Complex pruned transform along the middle axis of [outer][N][inner] -> [outer][L][inner]
 // ------------------------------------------------------------------------------------------
-template <int M>
+template <int M, bool STREAM>
 __global__ __launch_bounds__(kThreads) void axis_fwd_kernel(
     const float2* __restrict__ in, float2* __restrict__ out, const float2* __restrict__ tw, int N,
     int L, int npos, long long inner, int W, int ncb, int tw_lds) {
@@ -588,7 +588,7 @@ __global__ __launch_bounds__(kThreads) void axis_fwd_kernel(
       const float2* src = in + (o * N + n2) * inner + c0 + col;
       float2 a[M];
 #pragma unroll
-      for (int n1 = 0; n1 < M; ++n1) a[n1] = nt_load(&src[(long long)(P * n1) * inner]);
+      for (int n1 = 0; n1 < M; ++n1) a[n1] = ld_once2<STREAM>(&src[(long long)(P * n1) * inner]);
       fft_reg<M, -1>(a);
 #pragma unroll
       for (int m = 0; m < M; ++m) F[(P * m + n2) * W + col] = a[bitrev<M>(m)];
@@ -607,7 +607,7 @@ __global__ __launch_bounds__(kThreads) void axis_fwd_kernel(
 }
 
 // [outer][L][inner] (kept frequencies, zero elsewhere) -> [outer][N][inner], exp(+i...)
-template <int M>
+template <int M, bool STREAM>
 __global__ __launch_bounds__(kThreads) void axis_inv_kernel(
     const float2* __restrict__ in, float2* __restrict__ out, const float2* __restrict__ tw, int N,
     int L, int npos, long long inner, int W, int ncb, int tw_lds) {
@@ -656,7 +656,7 @@ __global__ __launch_bounds__(kThreads) void axis_inv_kernel(
       fft_reg<M, +1>(g);
       float2* dst = out + (o * N + n2) * inner + c0 + col;
 #pragma unroll
-      for (int n1 = 0; n1 < M; ++n1) nt_store(&dst[(long long)(P * n1) * inner], g[bitrev<M>(n1)]);
+      for (int n1 = 0; n1 < M; ++n1) st_once2<STREAM>(&dst[(long long)(P * n1) * inner], g[bitrev<M>(n1)]);
     }
   }
 }
@@ -674,7 +674,7 @@ constexpr int kMixB = 4;   // batch entries held per pass (backward mix)
 
 // One thread: one mode, KO output channels, KB batch entries per pass; R is read exactly once,
 // the input spectrum once per group of KO output channels (launch: grid.y = ceil(Co / KO)).
-template <int KB, int KO>
+template <int KB, int KO, bool STREAM>
 __global__ __launch_bounds__(kThreads) void mix_fwd_kernel(
     const float2* __restrict__ xh, const float2* __restrict__ R, float2* __restrict__ yh, int B,
     int Ci, int Co, long long K, int mt, int Nt, float invN) {
@@ -696,7 +696,7 @@ __global__ __launch_bounds__(kThreads) void mix_fwd_kernel(
 #pragma unroll
       for (int v = 0; v < KO; ++v) {
         if (o0 + v < Co) {
-          const float2 r = nt_load(&R[((long long)i * Co + o0 + v) * K + k]);
+          const float2 r = ld_once2<STREAM>(&R[((long long)i * Co + o0 + v) * K + k]);
 #pragma unroll
           for (int u = 0; u < KB; ++u) acc[u][v] = cfma(xv[u], r, acc[u][v]);
         }
@@ -714,6 +714,7 @@ __global__ __launch_bounds__(kThreads) void mix_fwd_kernel(
 // One thread: one mode k, kMixI input channels, the batch in chunks of kMixB; the gradient
 // spectrum gh is then read once per kMixI input channels.
 constexpr int kMixI = 4;
+template <bool STREAM>
 __global__ __launch_bounds__(kThreads) void mix_bwd_kernel(
     const float2* __restrict__ xh, const float2* __restrict__ R, const float2* __restrict__ gh,
     float2* __restrict__ gR, float2* __restrict__ gxh, int B, int Ci, int Co, long long K, int mt,
@@ -737,7 +738,7 @@ __global__ __launch_bounds__(kThreads) void mix_bwd_kernel(
 #pragma unroll
       for (int v = 0; v < kMixI; ++v) {
         const long long ridx = ((long long)(i0 + v) * Co + o) * K + k;
-        r[v] = i0 + v < Ci ? nt_load(&R[ridx]) : make_float2(0.f, 0.f);
+        r[v] = i0 + v < Ci ? ld_once2<STREAM>(&R[ridx]) : make_float2(0.f, 0.f);
         gr[v] = (gR != nullptr && (b0 > 0 || accumulate) && i0 + v < Ci) ? gR[ridx] : make_float2(0.f, 0.f);
       }
 #pragma unroll
@@ -755,7 +756,7 @@ __global__ __launch_bounds__(kThreads) void mix_bwd_kernel(
       if (gR != nullptr) {
 #pragma unroll
         for (int v = 0; v < kMixI; ++v)
-          if (i0 + v < Ci) nt_store(&gR[((long long)(i0 + v) * Co + o) * K + k], gr[v]);
+          if (i0 + v < Ci) st_once2<STREAM>(&gR[((long long)(i0 + v) * Co + o) * K + k], gr[v]);
       }
     }
     if (gxh != nullptr) {
@@ -835,10 +836,16 @@ hipError_t launch_tz_fwd(const float* x, float2* out, const float2* twt, const f
     const int64_t nblk = (((planes + ppb - 1) / ppb + 7) / 8) * 8;
     if (nblk > 0x7fffffffLL) return hipErrorInvalidValue;
     const int inv_mt = (65536 + mt - 1) / mt;
-#define FNO_TZF_C(NTV, MZV, MTV, LZV, NPV, PZV, THRV)                                                         \
-  hipLaunchKernelGGL((tz_fwd_fast_kernel<NTV, MZV, MTV, LZV, NPV, PZV, THRV>), dim3((unsigned)nblk), dim3(thr), \
-                     lds, s, x, out, twz, (long long)planes, az.N, az.L, az.npos, mt, ppb, region,            \
+    const bool stream = planes * (int64_t)az.N * Nt * 4 >= kStreamBytes;
+#define FNO_TZF_S(NTV, MZV, MTV, LZV, NPV, PZV, THRV, STRV)                                                   \
+  hipLaunchKernelGGL((tz_fwd_fast_kernel<NTV, MZV, MTV, LZV, NPV, PZV, THRV, STRV>), dim3((unsigned)nblk),      \
+                     dim3(thr), lds, s, x, out, twz, (long long)planes, az.N, az.L, az.npos, mt, ppb, region, \
                      ilog2(az.P), inv_mt)
+#define FNO_TZF_C(NTV, MZV, MTV, LZV, NPV, PZV, THRV)                \
+  do {                                                               \
+    if (stream) FNO_TZF_S(NTV, MZV, MTV, LZV, NPV, PZV, THRV, true); \
+    else FNO_TZF_S(NTV, MZV, MTV, LZV, NPV, PZV, THRV, false);       \
+  } while (0)
 #define FNO_TZF(NTV, MZV) FNO_TZF_C(NTV, MZV, 0, 0, 0, -1, 0)
 #define FNO_TZF_M(NTV)                     \
   do {                                     \
@@ -857,6 +864,7 @@ hipError_t launch_tz_fwd(const float* x, float2* out, const float2* twt, const f
 #undef FNO_TZF_M
 #undef FNO_TZF
 #undef FNO_TZF_C
+#undef FNO_TZF_S
     return hipGetLastError();
   }
   if (az.M == 1 && Nt % 4 == 0 && mt <= 16 && (reinterpret_cast<uintptr_t>(x) & 15) == 0) {
@@ -897,9 +905,16 @@ hipError_t launch_axis_fwd(const float2* in, float2* out, const float2* tw, int6
   // the twiddles go to LDS only when that does not cost a resident block
   const int tw_lds = (size_t)ax.L * ax.P * 8 <= (size_t)(8 * 1024) && (size_t)ax.N * W * 8 <= (size_t)(16 * 1024);
   const size_t lds = (size_t)ax.N * W * 8 + (tw_lds ? (size_t)ax.L * ax.P * 8 : 0);
-  FNO_DISPATCH_M(ax.M, hipLaunchKernelGGL((axis_fwd_kernel<MM>), dim3((unsigned)nblk),
-                                          dim3(kThreads), lds, s, in, out, tw, ax.N, ax.L, ax.npos,
-                                          (long long)inner, W, (int)ncb, tw_lds));
+  // the input is read once: as a stream when it is larger than the caches
+  if (outer * ax.N * inner * 8 >= kStreamBytes) {
+    FNO_DISPATCH_M(ax.M, hipLaunchKernelGGL((axis_fwd_kernel<MM, true>), dim3((unsigned)nblk),
+                                            dim3(kThreads), lds, s, in, out, tw, ax.N, ax.L, ax.npos,
+                                            (long long)inner, W, (int)ncb, tw_lds));
+  } else {
+    FNO_DISPATCH_M(ax.M, hipLaunchKernelGGL((axis_fwd_kernel<MM, false>), dim3((unsigned)nblk),
+                                            dim3(kThreads), lds, s, in, out, tw, ax.N, ax.L, ax.npos,
+                                            (long long)inner, W, (int)ncb, tw_lds));
+  }
   return hipGetLastError();
 }
 
@@ -913,9 +928,16 @@ hipError_t launch_axis_inv(const float2* in, float2* out, const float2* tw, int6
   const int tw_lds = (size_t)ax.L * ax.P * 8 <= (size_t)(8 * 1024);
   const size_t lds = (size_t)ax.L * W * 8 + (tw_lds ? (size_t)ax.L * ax.P * 8 : 0);
   const int thr = axis_threads(ax.P * W);
-  FNO_DISPATCH_M(ax.M, hipLaunchKernelGGL((axis_inv_kernel<MM>), dim3((unsigned)nblk),
-                                          dim3(thr), lds, s, in, out, tw, ax.N, ax.L, ax.npos,
-                                          (long long)inner, W, (int)ncb, tw_lds));
+  // the output is written once: as a stream when it is larger than the caches
+  if (outer * ax.N * inner * 8 >= kStreamBytes) {
+    FNO_DISPATCH_M(ax.M, hipLaunchKernelGGL((axis_inv_kernel<MM, true>), dim3((unsigned)nblk),
+                                            dim3(thr), lds, s, in, out, tw, ax.N, ax.L, ax.npos,
+                                            (long long)inner, W, (int)ncb, tw_lds));
+  } else {
+    FNO_DISPATCH_M(ax.M, hipLaunchKernelGGL((axis_inv_kernel<MM, false>), dim3((unsigned)nblk),
+                                            dim3(thr), lds, s, in, out, tw, ax.N, ax.L, ax.npos,
+                                            (long long)inner, W, (int)ncb, tw_lds));
+  }
   return hipGetLastError();
 }
 
@@ -925,8 +947,13 @@ hipError_t launch_mix_fwd(const float2* xh, const float2* R, float2* yh, int B, 
   if (nb > 0x7fffffffLL || Co > 65535) return hipErrorInvalidValue;
   // four output channels and four batch entries per thread; wider output tiles (10 or 20 channels
   // for a single batch entry, which would read the input spectrum less often) measured slower
-  hipLaunchKernelGGL((mix_fwd_kernel<4, 4>), dim3((unsigned)nb, (unsigned)((Co + 3) / 4)), dim3(kThreads), 0, s, xh, R,
-                     yh, B, Ci, Co, (long long)K, mt, Nt, (float)invN);
+  // R is read once per call: as a stream when it is larger than the caches
+  if ((int64_t)Ci * Co * K * 8 >= kStreamBytes)
+    hipLaunchKernelGGL((mix_fwd_kernel<4, 4, true>), dim3((unsigned)nb, (unsigned)((Co + 3) / 4)), dim3(kThreads), 0, s,
+                       xh, R, yh, B, Ci, Co, (long long)K, mt, Nt, (float)invN);
+  else
+    hipLaunchKernelGGL((mix_fwd_kernel<4, 4, false>), dim3((unsigned)nb, (unsigned)((Co + 3) / 4)), dim3(kThreads), 0, s,
+                       xh, R, yh, B, Ci, Co, (long long)K, mt, Nt, (float)invN);
   return hipGetLastError();
 }
 
@@ -935,8 +962,12 @@ hipError_t launch_mix_bwd(const float2* xh, const float2* R, const float2* gh, f
                           double invN, int accumulate, hipStream_t s) {
   const int64_t nb = (K + kThreads - 1) / kThreads;
   if (nb > 0x7fffffffLL || Ci > 4 * 65535) return hipErrorInvalidValue;
-  hipLaunchKernelGGL(mix_bwd_kernel, dim3((unsigned)nb, (unsigned)((Ci + kMixI - 1) / kMixI)), dim3(kThreads), 0, s, xh, R,
-                     gh, gR, gxh, B, Ci, Co, (long long)K, mt, Nt, (float)invN, accumulate);
+  if ((int64_t)Ci * Co * K * 8 >= kStreamBytes)
+    hipLaunchKernelGGL(mix_bwd_kernel<true>, dim3((unsigned)nb, (unsigned)((Ci + kMixI - 1) / kMixI)), dim3(kThreads), 0,
+                       s, xh, R, gh, gR, gxh, B, Ci, Co, (long long)K, mt, Nt, (float)invN, accumulate);
+  else
+    hipLaunchKernelGGL(mix_bwd_kernel<false>, dim3((unsigned)nb, (unsigned)((Ci + kMixI - 1) / kMixI)), dim3(kThreads), 0,
+                       s, xh, R, gh, gR, gxh, B, Ci, Co, (long long)K, mt, Nt, (float)invN, accumulate);
   return hipGetLastError();
 }
 

@@ -20,7 +20,7 @@ namespace {
 // the pre-activation is stored as well), EPI = -1 reads it from the arguments.  With a fixed
 // epilogue every half step issues the same number of loads and stores on every path, which the
 // compiler's wait counts for the prefetched u values rely on.
-template <int CT, bool FULL, int MTC, int LZC, int NPC, int EPI>
+template <int CT, bool FULL, int MTC, int LZC, int NPC, int EPI, bool STREAM>
 __global__ __launch_bounds__(512, 4) void zt_inv_col_kernel(
     const float2* __restrict__ a, float* __restrict__ out, int Co_rt, int NxNy, int Nz, int Lz_rt,
     int nposz_rt, int mt_rt, int inv_mt, int a_floats, int a_stride4, int v_stride,
@@ -95,7 +95,7 @@ __global__ __launch_bounds__(512, 4) void zt_inv_col_kernel(
     for (int sl = 0; sl < 2; ++sl)
 #pragma unroll
       for (int i = 0; i < CI; ++i)
-        if (FULL || i < Cu) xv[i][sl] = __builtin_nontemporal_load(&ubase[i * Npts + sl * NT]);
+        if (FULL || i < Cu) xv[i][sl] = ld_once<STREAM>(&ubase[i * Npts + sl * NT]);
   }
   asm volatile("" ::: "memory");
   // everything issued so far has landed (the first u values too: the bias step below reads LDS that
@@ -228,7 +228,7 @@ __global__ __launch_bounds__(512, 4) void zt_inv_col_kernel(
         if constexpr (PREFETCH) {
 #pragma unroll
           for (int i = 0; i < CI; ++i)
-            if (FULL || i < Cu) xv[i][sl] = __builtin_nontemporal_load(&ubase[i * Npts + (n2 + 2) * NT]);
+            if (FULL || i < Cu) xv[i][sl] = ld_once<STREAM>(&ubase[i * Npts + (n2 + 2) * NT]);
         }
         asm volatile("" ::: "memory");
       }
@@ -239,19 +239,20 @@ __global__ __launch_bounds__(512, 4) void zt_inv_col_kernel(
 #pragma unroll
         for (int T = 0; T < CT; ++T)
           if (FULL || 4 * T + j4 < Co)
-            __builtin_nontemporal_store(acc[T], reinterpret_cast<v4f*>(zp + (4 * T) * Npts));
+            st_once<STREAM>(reinterpret_cast<v4f*>(zp + (4 * T) * Npts), acc[T]);
       }
       if (act) {
 #pragma unroll
         for (int T = 0; T < CT; ++T)
           if (FULL || 4 * T + j4 < Co)
-            __builtin_nontemporal_store(v4f{gelu_fast_f(acc[T][0]), gelu_fast_f(acc[T][1]), gelu_fast_f(acc[T][2]),
-                                            gelu_fast_f(acc[T][3])}, reinterpret_cast<v4f*>(op + (4 * T) * Npts));
+            st_once<STREAM>(reinterpret_cast<v4f*>(op + (4 * T) * Npts),
+                            v4f{gelu_fast_f(acc[T][0]), gelu_fast_f(acc[T][1]), gelu_fast_f(acc[T][2]),
+                                gelu_fast_f(acc[T][3])});
       } else {
 #pragma unroll
         for (int T = 0; T < CT; ++T)
           if (FULL || 4 * T + j4 < Co)
-            __builtin_nontemporal_store(acc[T], reinterpret_cast<v4f*>(op + (4 * T) * Npts));
+            st_once<STREAM>(reinterpret_cast<v4f*>(op + (4 * T) * Npts), acc[T]);
       }
     }
   };
@@ -284,10 +285,17 @@ hipError_t launch_zt_inv_col(const float2* a, float* out, const float2* twt, con
                                          Cu, 4 * CT, mt, Nt, Nt, az.L, az.P, az.P, blob_floats, s);
       if (terr != hipSuccess) return terr;
       const dim3 grid((unsigned)NxNy, (unsigned)B);
-#define FNO_ZTC(CTV, FULLV, MTV, LZV, NPV, EPIV)                                                            \
-  hipLaunchKernelGGL((zt_inv_col_kernel<CTV, FULLV, MTV, LZV, NPV, EPIV>), grid, dim3(512), lds, s, a, out, Co, \
-                     NxNy, az.N, az.L, az.npos, mt, inv_mt, a_floats, a_stride4, v_stride, tables,         \
+#define FNO_ZTC_S(CTV, FULLV, MTV, LZV, NPV, EPIV, STRV)                                                     \
+  hipLaunchKernelGGL((zt_inv_col_kernel<CTV, FULLV, MTV, LZV, NPV, EPIV, STRV>), grid, dim3(512), lds, s, a, out, \
+                     Co, NxNy, az.N, az.L, az.npos, mt, inv_mt, a_floats, a_stride4, v_stride, tables,       \
                      blob_floats, e)
+      // u is read once and the results are written once: as streams when they are larger than the caches
+      const bool stream = (int64_t)B * Co * NxNy * az.N * Nt * 4 >= kStreamBytes;
+#define FNO_ZTC(CTV, FULLV, MTV, LZV, NPV, EPIV)                  \
+  do {                                                            \
+    if (stream) FNO_ZTC_S(CTV, FULLV, MTV, LZV, NPV, EPIV, true); \
+    else FNO_ZTC_S(CTV, FULLV, MTV, LZV, NPV, EPIV, false);       \
+  } while (0)
       // the shape of the large workloads (width 20, 9 kept t bins, 32 kept z frequencies) with its three
       // epilogues: forward, forward that keeps the pre-activation, and the adjoint's linear one
       const int epi = (e.act ? 1 : 0) | (e.zsave != nullptr ? 2 : 0);
@@ -302,6 +310,7 @@ hipError_t launch_zt_inv_col(const float2* a, float* out, const float2* twt, con
       } else if (CT == 2) { if (full) FNO_ZTC(2, true, 0, 0, 0, -1); else FNO_ZTC(2, false, 0, 0, 0, -1); }
       else { if (full) FNO_ZTC(5, true, 0, 0, 0, -1); else FNO_ZTC(5, false, 0, 0, 0, -1); }
 #undef FNO_ZTC
+#undef FNO_ZTC_S
       *taken = true;
       return hipGetLastError();
     }
