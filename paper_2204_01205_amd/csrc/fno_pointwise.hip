@@ -795,7 +795,7 @@ __global__ __launch_bounds__(kThreads) void adam_kernel(
 //   r_c = sum_j W_c[c][j].
 // One thread: one spatial point and four consecutive t; the output (the only large tensor) is
 // written once, a is read through the cache by the threads that share a point.
-template <int CO>
+template <int CO, bool STREAM>
 __global__ __launch_bounds__(kThreads) void time_lift_kernel(
     int Ci, int Co, long long np, int Nt, const float* __restrict__ a, const float* __restrict__ wt,
     const float* __restrict__ bt, const float* __restrict__ wc, const float* __restrict__ bc,
@@ -836,7 +836,7 @@ __global__ __launch_bounds__(kThreads) void time_lift_kernel(
       for (int u = 0; u < 4; ++u) v[u] = fmaf(w4[u], sc[c], fmaf(b4[u], rc[c], bias));
       float* dst = out + ((b * Co + c) * np + p) * Nt + t0;
       if (vec) {
-        *reinterpret_cast<float4*>(dst) = make_float4(v[0], v[1], v[2], v[3]);
+        st_once<STREAM>(reinterpret_cast<v4f*>(dst), v4f{v[0], v[1], v[2], v[3]});
       } else {
 #pragma unroll
         for (int u = 0; u < 4; ++u)
@@ -854,7 +854,7 @@ __global__ __launch_bounds__(kThreads) void time_lift_kernel(
 // value a[b][i][s] is the same for all its lanes; a chunk of space positions per block row, fp32
 // sums of 64 terms added into doubles, one partial per (chunk, pair) in a fixed order.
 constexpr int kLiftChunks = 1024;      // partial-sum slots of the sweep
-template <int CI>
+template <int CI, bool STREAM>
 __global__ __launch_bounds__(kThreads) void time_lift_bwd_kernel(
     int Ci, int Co, long long S, int Nt, int cpb, const float* __restrict__ a, const float* __restrict__ g,
     double* __restrict__ part) {
@@ -880,7 +880,7 @@ __global__ __launch_bounds__(kThreads) void time_lift_bwd_kernel(
     for (; sp + 8 <= se; sp += 8) {              // eight positions per pass: their loads go out together
       float gv[8];
 #pragma unroll
-      for (int u = 0; u < 8; ++u) gv[u] = live ? gp[(sp + u) * Nt] : 0.f;
+      for (int u = 0; u < 8; ++u) gv[u] = live ? ld_once<STREAM>(&gp[(sp + u) * Nt]) : 0.f;
 #pragma unroll
       for (int u = 0; u < 8; ++u) {
         f0 += gv[u];
@@ -1127,15 +1127,19 @@ hipError_t launch_time_lift(int B, int Ci, int Co, int64_t np, int Nt, const flo
   // float4 stores need whole quads per row and an aligned tensor
   if ((Nt & 3) == 0 && (reinterpret_cast<uintptr_t>(out) & 15) != 0) return hipErrorInvalidValue;
   dim3 grid((unsigned)nb, (unsigned)B);
-  if (Co <= 8)
-    hipLaunchKernelGGL((time_lift_kernel<8>), grid, dim3(kThreads), 0, s, Ci, Co, (long long)np, Nt, a, wt,
-                       bt, wc, bc, out);
-  else if (Co <= 20)
-    hipLaunchKernelGGL((time_lift_kernel<20>), grid, dim3(kThreads), 0, s, Ci, Co, (long long)np, Nt, a, wt,
-                       bt, wc, bc, out);
-  else
-    hipLaunchKernelGGL((time_lift_kernel<32>), grid, dim3(kThreads), 0, s, Ci, Co, (long long)np, Nt, a, wt,
-                       bt, wc, bc, out);
+  // the lifted tensor is written once: as a stream when it is larger than the caches
+  const bool stream = (int64_t)B * Co * np * Nt * 4 >= kStreamBytes;
+#define FNO_TL(COV)                                                                                          \
+  do {                                                                                                       \
+    if (stream)                                                                                              \
+      hipLaunchKernelGGL((time_lift_kernel<COV, true>), grid, dim3(kThreads), 0, s, Ci, Co, (long long)np, Nt, a, \
+                         wt, bt, wc, bc, out);                                                               \
+    else                                                                                                     \
+      hipLaunchKernelGGL((time_lift_kernel<COV, false>), grid, dim3(kThreads), 0, s, Ci, Co, (long long)np, Nt, a, \
+                         wt, bt, wc, bc, out);                                                               \
+  } while (0)
+  if (Co <= 8) FNO_TL(8); else if (Co <= 20) FNO_TL(20); else FNO_TL(32);
+#undef FNO_TL
   return hipGetLastError();
 }
 
@@ -1155,9 +1159,17 @@ hipError_t launch_time_lift_bwd(int B, int Ci, int Co, int64_t S, int Nt, const 
   double* part = static_cast<double*>(ws);
   double* G = part + (size_t)kLiftChunks * nent;
   const dim3 grid((unsigned)((npair + kThreads - 1) / kThreads), (unsigned)nchunk);
-#define FNO_TLB(CIV)                                                                                        \
-  hipLaunchKernelGGL((time_lift_bwd_kernel<CIV>), grid, dim3(kThreads), 0, s, Ci, Co, (long long)S, Nt, cpb, \
-                     a, g, part)
+  // the cotangent of the lifted tensor is read once: as a stream when it is larger than the caches
+  const bool stream = (int64_t)B * Co * S * Nt * 4 >= kStreamBytes;
+#define FNO_TLB(CIV)                                                                                         \
+  do {                                                                                                       \
+    if (stream)                                                                                              \
+      hipLaunchKernelGGL((time_lift_bwd_kernel<CIV, true>), grid, dim3(kThreads), 0, s, Ci, Co, (long long)S, Nt, \
+                         cpb, a, g, part);                                                                   \
+    else                                                                                                     \
+      hipLaunchKernelGGL((time_lift_bwd_kernel<CIV, false>), grid, dim3(kThreads), 0, s, Ci, Co, (long long)S, Nt, \
+                         cpb, a, g, part);                                                                   \
+  } while (0)
   if (Ci == 1) FNO_TLB(1); else if (Ci == 2) FNO_TLB(2); else if (Ci <= 4) FNO_TLB(4); else FNO_TLB(8);
 #undef FNO_TLB
   hipLaunchKernelGGL(time_lift_bwd_reduce_kernel, dim3((nent + 31) / 32), dim3(kThreads), 0, s, part, nchunk,
