@@ -806,7 +806,7 @@ hipError_t launch_plan_tables(const TableSet& ts, hipStream_t s) {
 
 int tz_fast_region(AxisPlan az, int Nt, int mt, int ppb) {
   const int s_floats = ppb * az.N * Nt;
-  const int t_floats = 2 * ppb * mt * (az.N + 1);
+  const int t_floats = 2 * ppb * mt * tz_row_stride(az.N);
   const int r = s_floats > t_floats ? s_floats : t_floats;
   return (r + 255) & ~255;
 }
