@@ -88,6 +88,8 @@ SMALL = [
     (1, 8, 8, (2, 3, 64, 16), (1, 1, 8, 5), 0),        # same, width 8: one pass
     (2, 3, 5, (3, 2, 128, 16), (1, 1, 10, 7), 0),      # same, padded channel tiles, Cin != Cout
     (1, 6, 6, (2, 2, 64, 16), (1, 1, 5, 4), 0),        # same, padded channel tiles in a block
+    (1, 2, 2, (2, 2, 16, 64), (1, 1, 4, 9), 0),        # 64-point t axis (forward: the in-register 64-point real transform)
+    (1, 2, 2, (2, 2, 256, 16), (1, 1, 20, 5), 0),      # 256-point z axis: one plane fills the forward block, 16 residue classes
     (2, 2, 2, (2, 2, 8, 32), (1, 1, 4, 17), 0),        # 8-point z axis under 32 t points: the forward tile's row stride (17) exceeds N + 1
     (1, 8, 8, (3, 2, 32, 30), (1, 1, 4, 8), 0),        # matrix-core inverse kernel, t axis padded 30 -> 32
     (2, 3, 3, (2, 3, 32, 12), (1, 1, 6, 4), 0),        # same, 12 -> 16, padded channel tiles
