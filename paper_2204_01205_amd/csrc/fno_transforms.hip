@@ -821,7 +821,7 @@ hipError_t launch_tz_fwd(const float* x, float2* out, const float2* twt, const f
   if (planes <= 0) return hipSuccess;
   const bool fast = (Nt == 16 || Nt == 32 || Nt == 64) && (az.M == 8 || az.M == 16) &&
                     (az.P & (az.P - 1)) == 0 && (az.N * Nt) % 256 == 0 && (az.L * az.P) % 2 == 0 &&
-                    az.L * mt < 7000 && az.N <= kThreads &&
+                    (int64_t)az.L * mt * mt < 65536 && az.N <= kThreads &&   // the kernel's multiply-shift division by mt is exact below that
                     ((reinterpret_cast<uintptr_t>(x) | reinterpret_cast<uintptr_t>(twz)) & 15) == 0 &&
                     tz_fast_lds(az, Nt, mt, 1) <= (size_t)kLdsBudget;
   if (fast) {
