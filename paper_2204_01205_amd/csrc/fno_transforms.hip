@@ -435,6 +435,41 @@ __device__ __forceinline__ void rfft_row_bins_r4(const float4 (&quads)[NT / 4], 
   rfft4_bins<NT>(D, mt, X, std::make_integer_sequence<int, NT / 2 + 1>{});
 }
 
+// Bins 0..mt-1 of the real-input transform of one row of NT floats for an even NT that is no
+// power of two: the plain sums, with x[n] and x[NT-n] folded (cos is even, sin odd in n), all
+// twiddles compile-time constants.
+//   Re X[k] = x[0] + (-1)^k x[NT/2] + sum_{0<n<NT/2} (x[n] + x[NT-n]) cos(2 pi k n / NT)
+//   Im X[k] =                       - sum_{0<n<NT/2} (x[n] - x[NT-n]) sin(2 pi k n / NT)
+template <int NT, int IDX> constexpr float kCosFrac = float(ct_cos_frac(IDX, NT));      // cos(2 pi IDX / NT)
+template <int NT, int IDX> constexpr float kNegSinFrac = float(-ct_sin_frac(IDX, NT)); // -sin(2 pi IDX / NT)
+
+template <int NT, int K, int... Ns>
+__device__ __forceinline__ float2 dense_bin(const float (&sm)[NT / 2], const float (&df)[NT / 2], float x0, float xh,
+                                            std::integer_sequence<int, Ns...>) {
+  float re = (K % 2 == 0) ? x0 + xh : x0 - xh, im = 0.f;
+  ((Ns > 0 ? (void)(re = fmaf(kCosFrac<NT, (K * Ns) % NT>, sm[Ns], re),
+                    im = fmaf(kNegSinFrac<NT, (K * Ns) % NT>, df[Ns], im))
+           : (void)0),
+   ...);
+  return make_float2(re, im);
+}
+
+template <int NT, int... Ks>
+__device__ __forceinline__ void dense_bins(const float (&sm)[NT / 2], const float (&df)[NT / 2], float x0, float xh, int mt,
+                                           float2 (&X)[NT / 2 + 1], std::integer_sequence<int, Ks...>) {
+  ((Ks < mt ? (void)(X[Ks] = dense_bin<NT, Ks>(sm, df, x0, xh, std::make_integer_sequence<int, NT / 2>{})) : (void)0), ...);
+}
+
+template <int NT>
+__device__ __forceinline__ void rdft_row_bins_dense(const float (&x)[NT], int mt, float2 (&X)[NT / 2 + 1]) {
+  constexpr int H = NT / 2;
+  float sm[H], df[H];
+  sm[0] = 0.f; df[0] = 0.f;
+#pragma unroll
+  for (int n = 1; n < H; ++n) { sm[n] = x[n] + x[NT - n]; df[n] = x[n] - x[NT - n]; }
+  dense_bins<NT>(sm, df, x[0], x[H], mt, X, std::make_integer_sequence<int, H + 1>{});
+}
+
 // One thread per z-row (blockDim.x >= ppb * Nz).  The planes and the z twiddles go straight to
 // LDS (16 bytes per lane, 1 KiB per wave instruction, nothing staged in registers).  Inside a
 // row the quads are stored rotated by the row number so that the row-per-thread reads of the
@@ -455,7 +490,8 @@ __global__ __launch_bounds__(kThreads) void tz_fwd_fast_kernel(
   const int Lz = LZC ? LZC : Lz_rt;
   const int nposz = LZC ? NPC : nposz_rt;
   const int pzshift = PZC >= 0 ? PZC : pzshift_rt;
-  constexpr int QPR = NT / 4;                  // quads per row
+  constexpr bool POW2 = (NT & (NT - 1)) == 0;  // else: an even length, rows unrotated, t stage as plain sums
+  constexpr int QPR = POW2 ? NT / 4 : 1;       // quads per row
   constexpr int ROT = 16 / QPR > 0 ? 16 / QPR : 1;   // rows that share a rotation
   constexpr int H = NT / 2;
   const int Pz = 1 << pzshift;
@@ -472,13 +508,23 @@ __global__ __launch_bounds__(kThreads) void tz_fwd_fast_kernel(
 
   {
     const float4* src = reinterpret_cast<const float4*>(x + plane0 * Nz * NT);
-    const int tot4 = np * Nz * QPR;            // a multiple of 64 (checked on the host)
-    for (int c0 = wave * 64; c0 < tot4; c0 += nthr) {
-      const int p4 = c0 + lane;
-      const int zl = p4 / QPR, sl = p4 - zl * QPR;
-      const int q = (sl - zl / ROT) & (QPR - 1);
-      __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(src + zl * QPR + q),
-                                       (__attribute__((address_space(3))) void*)(S + 4 * c0), 16, 0, STREAM ? 2 : 0);   // aux 2: nontemporal
+    if constexpr (POW2) {
+      const int tot4 = np * Nz * QPR;            // a multiple of 64 (checked on the host)
+      for (int c0 = wave * 64; c0 < tot4; c0 += nthr) {
+        const int p4 = c0 + lane;
+        const int zl = p4 / QPR, sl = p4 - zl * QPR;
+        const int q = (sl - zl / ROT) & (QPR - 1);
+        __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(src + zl * QPR + q),
+                                         (__attribute__((address_space(3))) void*)(S + 4 * c0), 16, 0, STREAM ? 2 : 0);   // aux 2: nontemporal
+      }
+    } else {
+      const int tot4 = (np * Nz * NT) >> 2;      // whole 16-byte pieces (Nz NT is a multiple of 4, checked on the host)
+      for (int c0 = wave * 64; c0 < tot4; c0 += nthr) {
+        const int p4 = c0 + lane;
+        if (p4 < tot4)
+          __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(src + p4),
+                                           (__attribute__((address_space(3))) void*)(S + 4 * c0), 16, 0, STREAM ? 2 : 0);
+      }
     }
     const float4* tsrc = reinterpret_cast<const float4*>(twz);
     const int tw4 = (Lz << pzshift) >> 1;      // float4 pieces of the twiddle table (Lz * Pz even)
@@ -496,12 +542,23 @@ __global__ __launch_bounds__(kThreads) void tz_fwd_fast_kernel(
   const bool live = tid < np * Nz;
   float2 X[H + 1];
   if (live) {
-    float4 quads[QPR];
+    if constexpr (POW2) {
+      float4 quads[QPR];
 #pragma unroll
-    for (int q = 0; q < QPR; ++q)
-      quads[q] = *reinterpret_cast<const float4*>(S + 4 * (tid * QPR + ((q + tid / ROT) & (QPR - 1))));
-    if constexpr (NT == 16 || NT == 32) rfft_row_bins_r4<NT>(quads, mt, X);
-    else rfft_row_bins<NT>(quads, mt, X);
+      for (int q = 0; q < QPR; ++q)
+        quads[q] = *reinterpret_cast<const float4*>(S + 4 * (tid * QPR + ((q + tid / ROT) & (QPR - 1))));
+      if constexpr (NT == 16 || NT == 32) rfft_row_bins_r4<NT>(quads, mt, X);
+      else rfft_row_bins<NT>(quads, mt, X);
+    } else {
+      // rows of NT floats start 8-byte aligned (NT even); 30 floats apart they spread over all banks
+      float xr[NT];
+#pragma unroll
+      for (int n = 0; n < NT; n += 2) {
+        const float2 v = *reinterpret_cast<const float2*>(S + tid * NT + n);
+        xr[n] = v.x; xr[n + 1] = v.y;
+      }
+      rdft_row_bins_dense<NT>(xr, mt, X);
+    }
   }
   __syncthreads();
   if (live) {
@@ -819,8 +876,11 @@ size_t tz_fast_lds(AxisPlan az, int Nt, int mt, int ppb) {
 hipError_t launch_tz_fwd(const float* x, float2* out, const float2* twt, const float2* twz,
                          int64_t planes, AxisPlan az, int Nt, int mt, hipStream_t s) {
   if (planes <= 0) return hipSuccess;
-  const bool fast = (Nt == 16 || Nt == 32 || Nt == 64) && (az.M == 8 || az.M == 16) &&
-                    (az.P & (az.P - 1)) == 0 && (az.N * Nt) % 256 == 0 && (az.L * az.P) % 2 == 0 &&
+  // in-register t stage: the power-of-two lengths, and 30 (the time steps of the paper's training samples)
+  // as plain sums with compile-time twiddles
+  const bool pow2_t = Nt == 16 || Nt == 32 || Nt == 64;
+  const bool fast = (pow2_t ? (az.N * Nt) % 256 == 0 : (Nt == 30 && (az.N * Nt) % 4 == 0 && mt <= 16)) &&
+                    (az.M == 8 || az.M == 16) && (az.P & (az.P - 1)) == 0 && (az.L * az.P) % 2 == 0 &&
                     (int64_t)az.L * mt * mt < 65536 && az.N <= kThreads &&   // the kernel's multiply-shift division by mt is exact below that
                     ((reinterpret_cast<uintptr_t>(x) | reinterpret_cast<uintptr_t>(twz)) & 15) == 0 &&
                     tz_fast_lds(az, Nt, mt, 1) <= (size_t)kLdsBudget;
@@ -860,7 +920,8 @@ hipError_t launch_tz_fwd(const float* x, float2* out, const float2* twt, const f
     else if (Nt == 16 && z128 && thr == 256) FNO_TZF_C(16, 16, 9, 32, 16, 3, 256);
     else if (Nt == 32 && z64 && mt == 9 && thr == 128) FNO_TZF_C(32, 16, 9, 24, 12, 2, 128);
     else if (Nt == 16 && z64 && mt == 8 && thr == 256) FNO_TZF_C(16, 16, 8, 24, 12, 2, 256);
-    else if (Nt == 16) FNO_TZF_M(16); else if (Nt == 32) FNO_TZF_M(32); else FNO_TZF_M(64);
+    else if (Nt == 16) FNO_TZF_M(16); else if (Nt == 32) FNO_TZF_M(32); else if (Nt == 64) FNO_TZF_M(64);
+    else FNO_TZF_M(30);
 #undef FNO_TZF_M
 #undef FNO_TZF
 #undef FNO_TZF_C
